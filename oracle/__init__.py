@@ -1,0 +1,240 @@
+"""CPU oracle for the GNN aggregation path -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes access to ``gnn_oracle.c`` plus the layer/model compositions.  Only the
+tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import this
+package; the GPU library never does, and this package never imports the GPU library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gnn_oracle.c")
+_LIB = os.path.join(_HERE, "libgnn_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile gnn_oracle.c with gcc -O2 (no OpenMP, no BLAS)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".{os.getpid()}.tmp"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.orc_aes_sum.restype = ctypes.c_int64
+        _lib.orc_ng_partition.restype = ctypes.c_int64
+        _lib.orc_eq5_wpt.restype = ctypes.c_double
+        _lib.orc_eq5_smem.restype = ctypes.c_int64
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+# ------------------------------------------------------------------ operations
+def aggregate_gcn(rowptr, colidx, ew, X, want_abs: bool = False):
+    """Eq. 2 aggregation: out = (CSR with weights ew) @ X.  ew None = unit weights."""
+    rowptr, colidx, X = _i32(rowptr), _i32(colidx), _f32(X)
+    ew = None if ew is None else _f32(ew)
+    n, dim = rowptr.size - 1, X.shape[1]
+    out = np.empty((n, dim), dtype=np.float32)
+    ab = np.empty((n, dim), dtype=np.float64) if want_abs else None
+    _L().orc_aggregate_gcn(ctypes.c_int32(n), _p(rowptr), _p(colidx), _p(ew), _p(X), ctypes.c_int32(dim),
+                           _p(out), _p(ab))
+    return (out, ab) if want_abs else out
+
+
+def aggregate_gin(rowptr, colidx, eps: float, X, want_abs: bool = False):
+    """Eq. 3 aggregation: out_i = (1+eps) x_i + sum_{j in N(i)} x_j."""
+    rowptr, colidx, X = _i32(rowptr), _i32(colidx), _f32(X)
+    n, dim = rowptr.size - 1, X.shape[1]
+    out = np.empty((n, dim), dtype=np.float32)
+    ab = np.empty((n, dim), dtype=np.float64) if want_abs else None
+    _L().orc_aggregate_gin(ctypes.c_int32(n), _p(rowptr), _p(colidx), ctypes.c_float(eps), _p(X),
+                           ctypes.c_int32(dim), _p(out), _p(ab))
+    return (out, ab) if want_abs else out
+
+
+def gemm_bias_act(A, W, b=None, relu: bool = False, want_abs: bool = False):
+    """Update phase: act(A @ W + b)."""
+    A, W = _f32(A), _f32(W)
+    b = None if b is None else _f32(b)
+    n, K = A.shape
+    M = W.shape[1]
+    assert W.shape[0] == K
+    out = np.empty((n, M), dtype=np.float32)
+    ab = np.empty((n, M), dtype=np.float64) if want_abs else None
+    _L().orc_gemm_bias_act(ctypes.c_int32(n), ctypes.c_int32(K), ctypes.c_int32(M), _p(A), _p(W), _p(b),
+                           ctypes.c_int32(1 if relu else 0), _p(out), _p(ab))
+    return (out, ab) if want_abs else out
+
+
+def bias_act(Z, b=None, relu: bool = False):
+    Z = _f32(Z)
+    b = None if b is None else _f32(b)
+    out = np.empty_like(Z)
+    _L().orc_bias_act(ctypes.c_int32(Z.shape[0]), ctypes.c_int32(Z.shape[1]), _p(Z), _p(b),
+                      ctypes.c_int32(1 if relu else 0), _p(out))
+    return out
+
+
+def gcn_norm(rowptr, colidx) -> np.ndarray:
+    """Eq. 2 weights 1/sqrt(d_i d_j), d = stored row length."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    ew = np.empty(colidx.size, dtype=np.float32)
+    _L().orc_gcn_norm(ctypes.c_int32(rowptr.size - 1), _p(rowptr), _p(colidx), _p(ew))
+    return ew
+
+
+def aes_sum(rowptr, colidx) -> int:
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    return int(_L().orc_aes_sum(ctypes.c_int32(rowptr.size - 1), _p(rowptr), _p(colidx)))
+
+
+def aes(rowptr, colidx) -> float:
+    """Eq. 4."""
+    nnz = int(rowptr[-1])
+    return aes_sum(rowptr, colidx) / nnz if nnz else 0.0
+
+
+def aes_threshold(n: int) -> int:
+    return int(_L().orc_aes_threshold(ctypes.c_int32(n)))
+
+
+def should_reorder(rowptr, colidx) -> bool:
+    n = len(rowptr) - 1
+    return bool(_L().orc_should_reorder(ctypes.c_int32(n), ctypes.c_int64(int(rowptr[-1])),
+                                        ctypes.c_int64(aes_sum(rowptr, colidx))))
+
+
+def ng_partition(rowptr, ngs: int):
+    """Sec. 4.1 neighbor groups: arrays (node, start, end), half-open CSR ranges."""
+    rowptr = _i32(rowptr)
+    n = rowptr.size - 1
+    cnt = int(_L().orc_ng_partition(ctypes.c_int32(n), _p(rowptr), ctypes.c_int32(ngs), None, None, None))
+    node = np.empty(cnt, dtype=np.int32)
+    start = np.empty(cnt, dtype=np.int32)
+    end = np.empty(cnt, dtype=np.int32)
+    _L().orc_ng_partition(ctypes.c_int32(n), _p(rowptr), ctypes.c_int32(ngs), _p(node), _p(start), _p(end))
+    return node, start, end
+
+
+def alg1_layout(ng_node, warp_per_block: int, dim: int):
+    """Algorithm 1: per neighbor group (slot index, float offset of the slot, leader flag)."""
+    ng_node = _i32(ng_node)
+    k = ng_node.size
+    slot = np.empty(k, dtype=np.int32)
+    addr = np.empty(k, dtype=np.int64)
+    leader = np.empty(k, dtype=np.uint8)
+    _L().orc_alg1_layout(ctypes.c_int64(k), _p(ng_node), ctypes.c_int32(warp_per_block), ctypes.c_int32(dim),
+                         _p(slot), _p(addr), _p(leader))
+    return slot, addr, leader
+
+
+def eq5_wpt(ngs: int, dim: int, dw: int) -> float:
+    return float(_L().orc_eq5_wpt(ctypes.c_int32(ngs), ctypes.c_int32(dim), ctypes.c_int32(dw)))
+
+
+def eq5_smem(tpb: int, tpw: int, dim: int) -> int:
+    return int(_L().orc_eq5_smem(ctypes.c_int32(tpb), ctypes.c_int32(tpw), ctypes.c_int32(dim)))
+
+
+def eq6_dw(dim: int, tpw: int) -> int:
+    return int(_L().orc_eq6_dw(ctypes.c_int32(dim), ctypes.c_int32(tpw)))
+
+
+def reorder(rowptr, colidx) -> Tuple[np.ndarray, np.ndarray]:
+    """Sec. 5.1 renumbering (always applied): perm[old] = new, iperm[new] = old."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    n = rowptr.size - 1
+    perm = np.empty(n, dtype=np.int32)
+    iperm = np.empty(n, dtype=np.int32)
+    rc = _L().orc_reorder(ctypes.c_int32(n), _p(rowptr), _p(colidx), _p(perm), _p(iperm))
+    assert rc == 0
+    return perm, iperm
+
+
+def apply_perm_csr(rowptr, colidx, perm, val=None):
+    rowptr, colidx, perm = _i32(rowptr), _i32(colidx), _i32(perm)
+    val = None if val is None else _f32(val)
+    n = rowptr.size - 1
+    rp2 = np.empty(n + 1, dtype=np.int32)
+    ci2 = np.empty(colidx.size, dtype=np.int32)
+    v2 = None if val is None else np.empty(colidx.size, dtype=np.float32)
+    _L().orc_apply_perm_csr(ctypes.c_int32(n), _p(rowptr), _p(colidx), _p(val), _p(perm), _p(rp2), _p(ci2), _p(v2))
+    return (rp2, ci2) if val is None else (rp2, ci2, v2)
+
+
+def permute_rows(X, perm) -> np.ndarray:
+    X, perm = _f32(X), _i32(perm)
+    Y = np.empty_like(X)
+    _L().orc_permute_rows(ctypes.c_int32(X.shape[0]), ctypes.c_int32(X.shape[1]), _p(perm), _p(X), _p(Y))
+    return Y
+
+
+# ------------------------------------------------------------------ layers and models
+# Order inside a layer follows Sec. 3.1: GCN reduces the dimension first (Update, then
+# Aggregation); GIN aggregates at full dimension, then updates.  Values between operations
+# are stored as float.
+def gcn_layer(rowptr, colidx, ew, X, W, b=None, relu: bool = False, want_abs: bool = False):
+    H = gemm_bias_act(X, W, None, False)
+    if want_abs:
+        Z, ab = aggregate_gcn(rowptr, colidx, ew, H, want_abs=True)
+        return bias_act(Z, b, relu), ab
+    return bias_act(aggregate_gcn(rowptr, colidx, ew, H), b, relu)
+
+
+def gin_layer(rowptr, colidx, eps, X, W, b=None, relu: bool = False, want_abs: bool = False):
+    A = aggregate_gin(rowptr, colidx, eps, X)
+    return gemm_bias_act(A, W, b, relu, want_abs=want_abs)
+
+
+def gcn_model(rowptr, colidx, ew, X, Ws: Sequence[np.ndarray], bs: Optional[Sequence] = None,
+              want_abs: bool = False):
+    """ReLU after every layer but the last."""
+    H = X
+    ab = None
+    for l, W in enumerate(Ws):
+        last = l == len(Ws) - 1
+        b = None if bs is None else bs[l]
+        if last and want_abs:
+            H, ab = gcn_layer(rowptr, colidx, ew, H, W, b, relu=False, want_abs=True)
+        else:
+            H = gcn_layer(rowptr, colidx, ew, H, W, b, relu=not last)
+    return (H, ab) if want_abs else H
+
+
+def gin_model(rowptr, colidx, eps, X, Ws: Sequence[np.ndarray], bs: Optional[Sequence] = None,
+              want_abs: bool = False):
+    H = X
+    ab = None
+    for l, W in enumerate(Ws):
+        last = l == len(Ws) - 1
+        b = None if bs is None else bs[l]
+        if last and want_abs:
+            H, ab = gin_layer(rowptr, colidx, eps, H, W, b, relu=False, want_abs=True)
+        else:
+            H = gin_layer(rowptr, colidx, eps, H, W, b, relu=not last)
+    return (H, ab) if want_abs else H
