@@ -1,0 +1,181 @@
+/*
+ * gnn.h -- C ABI of the MI355X (gfx950) GNN aggregation library.
+ *
+ * The library computes the Aggregation phase of a GNN layer (GNNAdvisor, arXiv 2006.06608):
+ * a CSR sparse x dense product over fp32 node embeddings, with the paper's 2D workload
+ * management (neighbor groups x dimension workers, Sec. 4), block-level scratch-memory
+ * accumulation with leader flush (Sec. 5.2, Algorithm 1), community-aware renumbering
+ * (Sec. 5.1) and a parameter model (Sec. 6), plus the dense Update so that a whole layer
+ * can be run.
+ *
+ * Conventions
+ *   - Every function returns GNN_OK (0) or a negative error code; none throws, aborts or
+ *     prints.  gnn_strerror() names a code; gnn_last_hip_error() gives the HIP status
+ *     behind the calling thread's last GNN_EHIP.
+ *   - "HOST" / "DEVICE" on a pointer says where the memory must live.  The caller owns
+ *     every buffer; the library allocates no device memory and keeps no state between calls.
+ *   - Matrices are row-major fp32; CSR indices are int32 (nnz < 2^31); n * dim is
+ *     addressed in 64 bits.  In and out buffers must not alias.
+ *   - DEVICE entry points only enqueue work on `stream` (a hipStream_t, NULL = the null
+ *     stream) and return without synchronising, unless stated otherwise.  Errors that can
+ *     be seen at enqueue time are returned; a malformed device-side CSR (rowptr[n] != nnz,
+ *     decreasing rowptr) is caught by the partition kernels, recorded in the workspace and
+ *     reported by gnn_workspace_status(); column indices outside [0, n) are only caught by
+ *     gnn_validate_csr_device(), which callers of untrusted graphs must run first.
+ */
+#ifndef GNN_MI355X_H
+#define GNN_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ---------------------------------------------------------------- */
+#define GNN_OK 0
+#define GNN_EINVAL (-1)     /* NULL or out-of-range argument                              */
+#define GNN_ECSR (-2)       /* malformed CSR                                              */
+#define GNN_EWORKSPACE (-3) /* workspace missing, misaligned (256 B) or too small         */
+#define GNN_EHIP (-4)       /* a HIP runtime call failed                                  */
+#define GNN_ELIMIT (-5)     /* parameters exceed a documented limit (LDS budget, sizes)   */
+#define GNN_ESTALE (-6)     /* GNN_FLAG_REUSE_PARTITION but the workspace holds no partition for (n, nnz, ngs) */
+
+/* ---- layer kinds (Sec. 3.1) ------------------------------------------------------ */
+#define GNN_GCN 0 /* Update (GEMM), then Aggregation (Eq. 2), then bias/activation */
+#define GNN_GIN 1 /* Aggregation (Eq. 3), then Update (GEMM + bias), then activation */
+
+/* ---- flags of the DEVICE entry points -------------------------------------------- */
+#define GNN_FLAG_REUSE_PARTITION 1u /* workspace already holds the neighbor partition for this
+                                       (rowptr, ngs), built by gnn_partition_build or by an earlier
+                                       call without this flag: the one-time preparation of Sec. 4.1 */
+#define GNN_FLAG_NO_BLOCK_OPT 2u    /* ablation (Sec. 7.4 "block-level optimization"): no scratch-memory
+                                       slots, no leaders; every neighbor group adds to global memory */
+#define GNN_FLAG_NO_XCD_REMAP 4u    /* keep the hardware's round-robin block-to-XCD order */
+
+/* ================================================================================== */
+/* HOST-side preparation                                                              */
+/* ================================================================================== */
+
+/* Community-aware node renumbering (Sec. 5.1).  HOST pointers; rowptr[n+1], colidx[nnz] a
+ * symmetric CSR.  Computes AES (Eq. 4) and applies the rule sqrt(AES) > floor(sqrt(n)/100);
+ * if it holds (or force != 0) clusters nodes by greedy modularity merging and numbers each
+ * merge tree depth-first.  perm[old] = new, iperm[new] = old (both int32[n], caller-owned;
+ * identity when no renumbering is done).  aes_out, did_reorder may be NULL.  Deterministic.
+ * Errors: GNN_EINVAL (NULL, n < 0), GNN_ECSR (rowptr[0] != 0, decreasing, colidx out of range). */
+int gnn_reorder(int32_t n, const int32_t *rowptr, const int32_t *colidx, int32_t *perm,
+                int32_t *iperm, double *aes_out, int *did_reorder, int force);
+
+/* Eq. 4 alone: sum over stored entries of |row - col| and its mean.  HOST pointers. */
+int gnn_aes(int32_t n, const int32_t *rowptr, const int32_t *colidx, int64_t *aes_sum, double *aes);
+
+/* Eq. 2 weights: ew[e] = 1/sqrt(d_i * d_j) for entry e = (i, j), d = stored row length (the
+ * CSR is expected to contain the self loops).  HOST pointers, ew float[nnz]. */
+int gnn_gcn_norm(int32_t n, const int32_t *rowptr, const int32_t *colidx, float *ew);
+
+/* Relabel a CSR by perm: row perm[i] of the result holds {perm[j]} ascending; val (may be
+ * NULL together with val2) travels with its entry.  HOST pointers, outputs caller-owned with
+ * the input's sizes. */
+int gnn_apply_perm_csr(int32_t n, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                       const int32_t *perm, int32_t *rowptr2, int32_t *colidx2, float *val2);
+
+/* The parameter model re-derived for 256 CUs / 64-lane wavefronts / 160 KB LDS (Sec. 6).
+ * Pure host function.  max_degree may be 0 (unknown).  Outputs: ngs (neighbor-group size),
+ * dw (lanes that share one neighbor row), waves_per_block. */
+int gnn_decide(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, int32_t *ngs, int32_t *dw,
+               int32_t *waves_per_block);
+
+/* Eq. 5 and Eq. 6 exactly as printed, for reporting: dw from (dim, tpw); WPT = ngs*dim/dw;
+ * SMEM = (tpb/tpw)*dim*4 bytes.  Any output may be NULL. */
+int gnn_paper_model(int32_t dim, int32_t tpw, int32_t tpb, int32_t ngs, int32_t *dw, double *wpt,
+                    int64_t *smem_bytes);
+
+/* ================================================================================== */
+/* DEVICE entry points                                                                */
+/* ================================================================================== */
+
+/* Bytes of DEVICE workspace (256-byte aligned) that the calls below need for a graph of n
+ * nodes / nnz entries, neighbor-group size ngs (0 = whatever the model may pick) and, for
+ * gnn_layer_forward, an intermediate of max_dim floats per node (0 for aggregation only). */
+size_t gnn_workspace_bytes(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs);
+
+/* Neighbor partitioning (Sec. 4.1): cuts every CSR row into groups of ngs consecutive entries
+ * and stores, per group, (target node, start, end) in `workspace` -- the paper's
+ * neighbor-partitioning graph store.  DEVICE rowptr.  One-time per (graph, ngs); later calls
+ * pass GNN_FLAG_REUSE_PARTITION.  ngs >= 1. */
+int gnn_partition_build(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t ngs, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/* Synchronises `stream` and reads the partition's status back: returns GNN_OK, or the error
+ * the device kernels recorded (GNN_ECSR, GNN_ESTALE).  num_ng / ngs may be NULL. */
+int gnn_workspace_status(const void *workspace, void *stream, int64_t *num_ng, int32_t *ngs);
+
+/* Copies the stored neighbor groups to HOST arrays of `capacity` entries each (synchronises).
+ * Returns GNN_ELIMIT if capacity < number of groups. */
+int gnn_partition_export(const void *workspace, void *stream, int64_t capacity, int32_t *ng_node,
+                         int32_t *ng_start, int32_t *ng_end);
+
+/* Block layout of Algorithm 1 as the aggregation kernel derives it for (dw, waves_per_block):
+ * per neighbor group its slot index inside its block and its leader flag, copied to HOST
+ * arrays of `capacity` entries (synchronises).  groups_per_block (may be NULL) receives the
+ * number of neighbor groups one block serves (Algorithm 1's warpPerBlock). */
+int gnn_block_layout_export(const void *workspace, void *stream, int32_t dim, int32_t dw,
+                            int32_t waves_per_block, int64_t capacity, int32_t *slot, uint8_t *leader,
+                            int32_t *groups_per_block);
+
+/* Checks a DEVICE CSR: rowptr[0] == 0, non-decreasing, rowptr[n] == nnz, 0 <= colidx < n.
+ * Synchronises.  Returns GNN_OK or GNN_ECSR. */
+int gnn_validate_csr_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                            void *stream);
+
+/* GCN aggregation (Eq. 2 without the weight matrix): out = A_hat X with
+ * out[i,:] = sum_{e in row i} ew[e] * X[colidx[e],:].  DEVICE pointers.  ew NULL = unit weights.
+ * X, out: float[n*dim], out fully overwritten (rows without entries become 0).
+ *   ngs  neighbor-group size, 0 = model's choice (Sec. 4.1, Sec. 6)
+ *   dw   dimension workers: lanes sharing one neighbor row, a power of two <= 64, 0 = model's
+ *        choice (Sec. 4.2); a wavefront serves 64/dw neighbor groups side by side
+ *   waves_per_block  1..16, 0 = model's choice (the paper's user-chosen threads-per-block / 64)
+ * Errors: GNN_EINVAL, GNN_EWORKSPACE, GNN_ELIMIT (LDS need above 64 KB), GNN_EHIP. */
+int gnn_aggregate_gcn(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                      const float *ew, const float *X, float *out, int32_t dim, int32_t ngs,
+                      int32_t dw, int32_t waves_per_block, uint32_t flags, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/* GIN aggregation (the argument of h in Eq. 3): out[i,:] = (1+eps) X[i,:] + sum_{j in N(i)} X[j,:].
+ * The CSR holds no self loops.  Other arguments as above. */
+int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, float eps,
+                      const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw,
+                      int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
+                      void *stream);
+
+/* Update phase alone (Sec. 2.1, w.a + b): out[n,M] = act(A[n,K] W[K,M] + b), fp32 MFMA.
+ * b NULL or float[M]; relu 0/1.  DEVICE pointers. */
+int gnn_update_gemm(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b,
+                    int relu, float *out, void *stream);
+
+/* One GNN layer (Eq. 1).  kind GNN_GCN: out = act(A_hat (X W) + b);  GNN_GIN:
+ * out = act(((1+eps) X + sum_N X) W + b).  X float[n*in_dim], W float[in_dim*out_dim] row-major,
+ * b NULL or float[out_dim], out float[n*out_dim].  The intermediate lives in the workspace
+ * (size it with max_dim = out_dim for GCN, in_dim for GIN).  ew is used by GNN_GCN only, eps by
+ * GNN_GIN only. */
+int gnn_layer_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                      const float *ew, float eps, const float *X, int32_t in_dim, const float *W,
+                      const float *b, int32_t out_dim, int relu, float *out, int32_t ngs, int32_t dw,
+                      int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
+                      void *stream);
+
+/* Row gather for renumbering: Y[perm[i],:] = X[i,:] (pass iperm to undo).  DEVICE pointers,
+ * perm int32[n]. */
+int gnn_permute_rows(int32_t n, int32_t dim, const int32_t *perm, const float *X, float *Y, void *stream);
+
+/* ---- diagnostics ------------------------------------------------------------------ */
+const char *gnn_strerror(int code);
+int gnn_last_hip_error(void);
+/* Library version as major*10000 + minor*100 + patch. */
+int gnn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GNN_MI355X_H */

@@ -199,16 +199,28 @@ def permute_rows(X, perm) -> np.ndarray:
 # Aggregation); GIN aggregates at full dimension, then updates.  Values between operations
 # are stored as float.
 def gcn_layer(rowptr, colidx, ew, X, W, b=None, relu: bool = False, want_abs: bool = False):
-    H = gemm_bias_act(X, W, None, False)
-    if want_abs:
-        Z, ab = aggregate_gcn(rowptr, colidx, ew, H, want_abs=True)
-        return bias_act(Z, b, relu), ab
-    return bias_act(aggregate_gcn(rowptr, colidx, ew, H), b, relu)
+    """act(A_hat (X W) + b).  want_abs adds the layer's error scale |A_hat| (|X| |W|) + |b|: the sum of
+    absolute values of all terms of both operations, against which a floating-point evaluation in
+    any order is judged."""
+    if not want_abs:
+        H = gemm_bias_act(X, W, None, False)
+        return bias_act(aggregate_gcn(rowptr, colidx, ew, H), b, relu)
+    H, Habs = gemm_bias_act(X, W, None, False, want_abs=True)
+    Z = aggregate_gcn(rowptr, colidx, ew, H)
+    scale = aggregate_gcn(rowptr, colidx, None if ew is None else np.abs(_f32(ew)), Habs.astype(np.float32)).astype(np.float64)
+    if b is not None:
+        scale = scale + np.abs(_f32(b)).astype(np.float64)
+    return bias_act(Z, b, relu), scale
 
 
 def gin_layer(rowptr, colidx, eps, X, W, b=None, relu: bool = False, want_abs: bool = False):
-    A = aggregate_gin(rowptr, colidx, eps, X)
-    return gemm_bias_act(A, W, b, relu, want_abs=want_abs)
+    """act(((1+eps) X + sum_N X) W + b).  want_abs adds the layer's error scale (|1+eps| |X| + sum_N |X|) |W| + |b|."""
+    if not want_abs:
+        return gemm_bias_act(aggregate_gin(rowptr, colidx, eps, X), W, b, relu)
+    A, Aabs = aggregate_gin(rowptr, colidx, eps, X, want_abs=True)
+    out = gemm_bias_act(A, W, b, relu)
+    scale = gemm_bias_act(Aabs.astype(np.float32), np.abs(_f32(W)), None if b is None else np.abs(_f32(b)), False)
+    return out, scale.astype(np.float64)
 
 
 def gcn_model(rowptr, colidx, ew, X, Ws: Sequence[np.ndarray], bs: Optional[Sequence] = None,

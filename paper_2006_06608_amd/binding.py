@@ -1,0 +1,283 @@
+"""ctypes binding with the same names as the C ABI (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+__all__ = [
+    "GnnError", "lib_path", "load", "exported_symbols",
+    "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_NO_XCD_REMAP",
+    "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
+    "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
+    "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
+    "gnn_update_gemm", "gnn_layer_forward", "gnn_permute_rows", "gnn_strerror", "gnn_version",
+    "alloc_workspace",
+]
+
+GNN_GCN, GNN_GIN = 0, 1
+GNN_FLAG_REUSE_PARTITION, GNN_FLAG_NO_BLOCK_OPT, GNN_FLAG_NO_XCD_REMAP = 1, 2, 4
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libgnn_mi355x.so")
+
+# every symbol include/gnn.h declares
+_SYMBOLS = [
+    "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
+    "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
+    "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
+    "gnn_update_gemm", "gnn_layer_forward", "gnn_permute_rows", "gnn_strerror", "gnn_last_hip_error",
+    "gnn_version",
+]
+
+
+class GnnError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {gnn_strerror(code)} (code {code})")
+        self.code = code
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def exported_symbols():
+    return list(_SYMBOLS)
+
+
+def load():
+    """Load the shared library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2006_06608_amd.build` "
+                "(or __graft_entry__.build()); there is no CPU fallback")
+        lib = ctypes.CDLL(_LIB_PATH)
+        lib.gnn_workspace_bytes.restype = ctypes.c_size_t
+        lib.gnn_strerror.restype = ctypes.c_char_p
+        for name in _SYMBOLS:
+            getattr(lib, name)  # AttributeError if the build lost a symbol
+        _lib = lib
+    return _lib
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def _i32(x): return ctypes.c_int32(int(x))
+def _i64(x): return ctypes.c_int64(int(x))
+def _u32(x): return ctypes.c_uint32(int(x))
+def _f32(x): return ctypes.c_float(float(x))
+def _sz(x): return ctypes.c_size_t(int(x))
+
+
+def _host(a: Optional[np.ndarray], dtype, name: str):
+    if a is None:
+        return None
+    if not isinstance(a, np.ndarray) or a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError(f"{name}: expected a C-contiguous numpy array of {np.dtype(dtype).name}")
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dev(t, dtype_name: str, name: str):
+    """Device pointer of a contiguous CUDA/HIP torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    import torch
+    want = {"int32": torch.int32, "float32": torch.float32, "uint8": torch.uint8}[dtype_name]
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != want or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous {dtype_name} tensor on the GPU")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise GnnError(rc, what)
+
+
+def gnn_strerror(code: int) -> str:
+    return load().gnn_strerror(ctypes.c_int(code)).decode()
+
+
+def gnn_version() -> int:
+    return int(load().gnn_version())
+
+
+# ------------------------------------------------------------------ host-side preparation
+def gnn_reorder(rowptr: np.ndarray, colidx: np.ndarray, force: bool = False):
+    """-> (perm, iperm, aes, did_reorder)"""
+    n = rowptr.size - 1
+    perm = np.empty(n, dtype=np.int32)
+    iperm = np.empty(n, dtype=np.int32)
+    aes = ctypes.c_double(0.0)
+    did = ctypes.c_int(0)
+    rc = load().gnn_reorder(_i32(n), _host(rowptr, np.int32, "rowptr"), _host(colidx, np.int32, "colidx"),
+                            _host(perm, np.int32, "perm"), _host(iperm, np.int32, "iperm"),
+                            ctypes.byref(aes), ctypes.byref(did), ctypes.c_int(1 if force else 0))
+    _check(rc, "gnn_reorder")
+    return perm, iperm, aes.value, bool(did.value)
+
+
+def gnn_aes(rowptr: np.ndarray, colidx: np.ndarray) -> Tuple[int, float]:
+    s = ctypes.c_int64(0)
+    a = ctypes.c_double(0.0)
+    rc = load().gnn_aes(_i32(rowptr.size - 1), _host(rowptr, np.int32, "rowptr"), _host(colidx, np.int32, "colidx"),
+                        ctypes.byref(s), ctypes.byref(a))
+    _check(rc, "gnn_aes")
+    return int(s.value), float(a.value)
+
+
+def gnn_gcn_norm(rowptr: np.ndarray, colidx: np.ndarray) -> np.ndarray:
+    ew = np.empty(colidx.size, dtype=np.float32)
+    rc = load().gnn_gcn_norm(_i32(rowptr.size - 1), _host(rowptr, np.int32, "rowptr"),
+                             _host(colidx, np.int32, "colidx"), _host(ew, np.float32, "ew"))
+    _check(rc, "gnn_gcn_norm")
+    return ew
+
+
+def gnn_apply_perm_csr(rowptr: np.ndarray, colidx: np.ndarray, perm: np.ndarray, val: Optional[np.ndarray] = None):
+    n = rowptr.size - 1
+    rp2 = np.empty(n + 1, dtype=np.int32)
+    ci2 = np.empty(colidx.size, dtype=np.int32)
+    v2 = None if val is None else np.empty(colidx.size, dtype=np.float32)
+    rc = load().gnn_apply_perm_csr(_i32(n), _host(rowptr, np.int32, "rowptr"), _host(colidx, np.int32, "colidx"),
+                                   _host(val, np.float32, "val"), _host(perm, np.int32, "perm"),
+                                   _host(rp2, np.int32, "rowptr2"), _host(ci2, np.int32, "colidx2"),
+                                   _host(v2, np.float32, "val2"))
+    _check(rc, "gnn_apply_perm_csr")
+    return (rp2, ci2) if val is None else (rp2, ci2, v2)
+
+
+def gnn_decide(n: int, nnz: int, max_degree: int, dim: int) -> Tuple[int, int, int]:
+    a, b, c = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = load().gnn_decide(_i32(n), _i64(nnz), _i32(max_degree), _i32(dim), ctypes.byref(a), ctypes.byref(b),
+                           ctypes.byref(c))
+    _check(rc, "gnn_decide")
+    return a.value, b.value, c.value
+
+
+def gnn_paper_model(dim: int, tpw: int, tpb: int, ngs: int) -> Tuple[int, float, int]:
+    dw, wpt, smem = ctypes.c_int32(0), ctypes.c_double(0.0), ctypes.c_int64(0)
+    rc = load().gnn_paper_model(_i32(dim), _i32(tpw), _i32(tpb), _i32(ngs), ctypes.byref(dw), ctypes.byref(wpt),
+                                ctypes.byref(smem))
+    _check(rc, "gnn_paper_model")
+    return dw.value, wpt.value, smem.value
+
+
+# ------------------------------------------------------------------ device entry points
+def gnn_workspace_bytes(n: int, nnz: int, max_dim: int = 0, ngs: int = 0) -> int:
+    return int(load().gnn_workspace_bytes(_i32(n), _i64(nnz), _i32(max_dim), _i32(ngs)))
+
+
+def alloc_workspace(n: int, nnz: int, max_dim: int = 0, ngs: int = 0, device="cuda"):
+    """A uint8 torch tensor of the size gnn_workspace_bytes asks for (torch allocations are 256-byte aligned)."""
+    import torch
+    nbytes = gnn_workspace_bytes(n, nnz, max_dim, ngs)
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def _ws(workspace):
+    return _dev(workspace, "uint8", "workspace"), _sz(0 if workspace is None else workspace.numel())
+
+
+def gnn_partition_build(n, nnz, rowptr, ngs, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    rc = load().gnn_partition_build(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"), _i32(ngs), wp, wb,
+                                    _stream(stream))
+    _check(rc, "gnn_partition_build")
+
+
+def gnn_workspace_status(workspace, stream=None, check: bool = True) -> Tuple[int, int, int]:
+    """-> (status code, num_ng, ngs); raises on a non-zero status unless check=False."""
+    num = ctypes.c_int64(0)
+    ngs = ctypes.c_int32(0)
+    rc = load().gnn_workspace_status(_dev(workspace, "uint8", "workspace"), _stream(stream), ctypes.byref(num),
+                                     ctypes.byref(ngs))
+    if check:
+        _check(rc, "gnn_workspace_status")
+    return rc, int(num.value), int(ngs.value)
+
+
+def gnn_partition_export(workspace, stream=None):
+    _, num_ng, _ = gnn_workspace_status(workspace, stream)
+    node = np.empty(num_ng, dtype=np.int32)
+    start = np.empty(num_ng, dtype=np.int32)
+    end = np.empty(num_ng, dtype=np.int32)
+    rc = load().gnn_partition_export(_dev(workspace, "uint8", "workspace"), _stream(stream), _i64(num_ng),
+                                     _host(node, np.int32, "ng_node"), _host(start, np.int32, "ng_start"),
+                                     _host(end, np.int32, "ng_end"))
+    _check(rc, "gnn_partition_export")
+    return node, start, end
+
+
+def gnn_block_layout_export(workspace, dim: int, dw: int, waves_per_block: int, stream=None):
+    """-> (slot int32[num_ng], leader uint8[num_ng], groups_per_block)"""
+    _, num_ng, _ = gnn_workspace_status(workspace, stream)
+    slot = np.empty(num_ng, dtype=np.int32)
+    leader = np.empty(num_ng, dtype=np.uint8)
+    gpb = ctypes.c_int32(0)
+    rc = load().gnn_block_layout_export(_dev(workspace, "uint8", "workspace"), _stream(stream), _i32(dim), _i32(dw),
+                                        _i32(waves_per_block), _i64(num_ng), _host(slot, np.int32, "slot"),
+                                        _host(leader, np.uint8, "leader"), ctypes.byref(gpb))
+    _check(rc, "gnn_block_layout_export")
+    return slot, leader, gpb.value
+
+
+def gnn_validate_csr_device(n, nnz, rowptr, colidx, stream=None):
+    rc = load().gnn_validate_csr_device(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"),
+                                        _dev(colidx, "int32", "colidx"), _stream(stream))
+    _check(rc, "gnn_validate_csr_device")
+
+
+def gnn_aggregate_gcn(n, nnz, rowptr, colidx, ew, X, out, dim, ngs=0, dw=0, waves_per_block=0, flags=0,
+                      workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    rc = load().gnn_aggregate_gcn(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"), _dev(colidx, "int32", "colidx"),
+                                  _dev(ew, "float32", "ew"), _dev(X, "float32", "X"), _dev(out, "float32", "out"),
+                                  _i32(dim), _i32(ngs), _i32(dw), _i32(waves_per_block), _u32(flags), wp, wb,
+                                  _stream(stream))
+    _check(rc, "gnn_aggregate_gcn")
+
+
+def gnn_aggregate_gin(n, nnz, rowptr, colidx, eps, X, out, dim, ngs=0, dw=0, waves_per_block=0, flags=0,
+                      workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    rc = load().gnn_aggregate_gin(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"), _dev(colidx, "int32", "colidx"),
+                                  _f32(eps), _dev(X, "float32", "X"), _dev(out, "float32", "out"), _i32(dim),
+                                  _i32(ngs), _i32(dw), _i32(waves_per_block), _u32(flags), wp, wb, _stream(stream))
+    _check(rc, "gnn_aggregate_gin")
+
+
+def gnn_update_gemm(n, K, M, A, W, b, relu, out, stream=None):
+    rc = load().gnn_update_gemm(_i32(n), _i32(K), _i32(M), _dev(A, "float32", "A"), _dev(W, "float32", "W"),
+                                _dev(b, "float32", "b"), ctypes.c_int(1 if relu else 0), _dev(out, "float32", "out"),
+                                _stream(stream))
+    _check(rc, "gnn_update_gemm")
+
+
+def gnn_layer_forward(kind, n, nnz, rowptr, colidx, ew, eps, X, in_dim, W, b, out_dim, relu, out, ngs=0, dw=0,
+                      waves_per_block=0, flags=0, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    rc = load().gnn_layer_forward(ctypes.c_int(kind), _i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"),
+                                  _dev(colidx, "int32", "colidx"), _dev(ew, "float32", "ew"), _f32(eps),
+                                  _dev(X, "float32", "X"), _i32(in_dim), _dev(W, "float32", "W"),
+                                  _dev(b, "float32", "b"), _i32(out_dim), ctypes.c_int(1 if relu else 0),
+                                  _dev(out, "float32", "out"), _i32(ngs), _i32(dw), _i32(waves_per_block),
+                                  _u32(flags), wp, wb, _stream(stream))
+    _check(rc, "gnn_layer_forward")
+
+
+def gnn_permute_rows(n, dim, perm, X, Y, stream=None):
+    rc = load().gnn_permute_rows(_i32(n), _i32(dim), _dev(perm, "int32", "perm"), _dev(X, "float32", "X"),
+                                 _dev(Y, "float32", "Y"), _stream(stream))
+    _check(rc, "gnn_permute_rows")

@@ -1,0 +1,537 @@
+// The aggregation kernels (Sec. 4 and Sec. 5.2) for gfx950, and the entry points built on them.
+//
+// Mapping.  A neighbor group (<= ngs consecutive CSR entries of one target node, Sec. 4.1) is
+// served by a team of dwl lanes (the dimension workers of Sec. 4.2); a 64-lane wavefront carries
+// 64/dwl teams side by side, so no lane idles when a row is shorter than a wavefront.  Each lane
+// owns VEC consecutive floats of up to ITER chunks of the row and reads them with one 4*VEC-byte
+// load per neighbor, U neighbors in flight.  A block of W waves serves T = W*64/dwl consecutive
+// groups; their CSR positions are contiguous, so the block stages that index range (and the edge
+// weights) in LDS with coalesced loads first.
+//
+// Reduction.  Teams of one wave that share a target node are combined with wavefront shuffles
+// (segmented reduction).  A node whose groups all sit in one wave is then stored straight from
+// registers.  Other nodes are accumulated in the block's LDS slots laid out as Algorithm 1
+// prescribes; after a barrier the leader team of each slot writes the row: a plain store when
+// the block saw all groups of the node, one global atomic add per element otherwise (only nodes
+// whose groups span several blocks, i.e. high-degree ones).  Rows that receive atomics, and rows
+// without any entry, are initialised by a small kernel that runs first.
+#include <hip/hip_runtime.h>
+
+#include "gnn_device.h"
+#include "gnn_internal.h"
+
+namespace gnn {
+
+int partition_build_impl(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t ngs, void *workspace,
+                         size_t workspace_bytes, hipStream_t s);
+
+struct AggParams {
+    WsHeader *hdr;
+    const NgEntry *ng;
+    const int *ngptr;
+    const int *colidx;
+    const float *ew;
+    const float *X;
+    float *out;
+    const float *bias;  // epilogue: out = act(sum + bias); may be null
+    float self_scale;   // 1 + eps (GIN)
+    int relu;
+    int n;
+    int dim;
+    int ngs;
+    int dwl_log2;
+    int T;           // neighbor groups per block
+    int iter_total;  // chunks of dwl*VEC floats per row
+    int xcd_remap;
+    int64_t nnz;
+};
+
+template <int VEC>
+__device__ __forceinline__ void load_vec(float (&r)[VEC], const float *p)
+{
+    if constexpr (VEC == 4) {
+        const float4 v = *reinterpret_cast<const float4 *>(p);
+        r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
+    } else if constexpr (VEC == 2) {
+        const float2 v = *reinterpret_cast<const float2 *>(p);
+        r[0] = v.x; r[1] = v.y;
+    } else {
+        r[0] = *p;
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(float *p, const float (&r)[VEC])
+{
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<float4 *>(p) = make_float4(r[0], r[1], r[2], r[3]);
+    } else if constexpr (VEC == 2) {
+        *reinterpret_cast<float2 *>(p) = make_float2(r[0], r[1]);
+    } else {
+        *p = r[0];
+    }
+}
+
+__device__ __forceinline__ bool header_ok(const WsHeader *hdr, const AggParams &p)
+{
+    return hdr->magic == kMagic && hdr->status == GNN_OK && hdr->ngs == p.ngs && hdr->n == p.n && hdr->nnz == p.nnz;
+}
+
+__device__ __forceinline__ float epilogue(float v, const float *bias, int d, int relu)
+{
+    if (bias) v += bias[d];
+    if (relu) v = fmaxf(v, 0.0f);
+    return v;
+}
+
+// Rows the main kernel will not store plainly: rows without entries get their final value, rows
+// whose groups span several blocks are zeroed for the atomic adds.  One wave scans 64 nodes.
+template <bool SELF>
+__global__ __launch_bounds__(256) void k_agg_init(AggParams p)
+{
+    WsHeader *hdr = p.hdr;
+    if (!header_ok(hdr, p)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            // record why nothing was computed
+            if (hdr->magic != kMagic) {
+                hdr->magic = kMagic;
+                hdr->n = p.n;
+                hdr->nnz = p.nnz;
+                hdr->ngs = 0;
+                hdr->num_ng = 0;
+                hdr->status = GNN_ESTALE;
+            } else if (hdr->status == GNN_OK) {
+                hdr->status = GNN_ESTALE;
+            }
+        }
+        return;
+    }
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t v = wave * 64 + lane;
+    int action = 0;
+    if (v < p.n) {
+        const int c0 = p.ngptr[v], c1 = p.ngptr[v + 1];
+        if (c1 == c0) action = 2;
+        else if (c0 / p.T != (c1 - 1) / p.T) action = 1;
+    }
+    unsigned long long m = __ballot(action != 0);
+    while (m) {
+        const int l = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        const int act = __shfl(action, l);
+        const int64_t node = wave * 64 + l;
+        float *row = p.out + (size_t)node * p.dim;
+        const float *xrow = p.X + (size_t)node * p.dim;
+        for (int d = lane; d < p.dim; d += 64) {
+            float val = 0.0f;
+            if (act == 2) {
+                if (SELF) val = p.self_scale * xrow[d];
+                val = epilogue(val, p.bias, d, p.relu);
+            }
+            row[d] = val;
+        }
+    }
+}
+
+// Bias/activation for the rows that were completed by atomic adds.
+__global__ __launch_bounds__(256) void k_agg_epilogue_spanning(AggParams p)
+{
+    if (!header_ok(p.hdr, p)) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t v = wave * 64 + lane;
+    int action = 0;
+    if (v < p.n) {
+        const int c0 = p.ngptr[v], c1 = p.ngptr[v + 1];
+        if (c1 > c0 && c0 / p.T != (c1 - 1) / p.T) action = 1;
+    }
+    unsigned long long m = __ballot(action != 0);
+    while (m) {
+        const int l = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        float *row = p.out + (size_t)(wave * 64 + l) * p.dim;
+        for (int d = lane; d < p.dim; d += 64) row[d] = epilogue(row[d], p.bias, d, p.relu);
+    }
+}
+
+template <int VEC, int ITER, int U, bool WEIGHTED, bool SELF>
+__global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const WsHeader *hdr = p.hdr;
+    if (!header_ok(hdr, p)) return;
+
+    const int T = p.T;
+    const int64_t num_ng = hdr->num_ng;
+    const int64_t tiles = (num_ng + T - 1) / T;
+    int64_t tile = blockIdx.x;
+    if (p.xcd_remap) {
+        // consecutive tiles (neighbouring node ids, hence shared neighbours after renumbering) go to
+        // the same XCD and its L2, instead of being dealt round-robin over the eight XCDs
+        const int64_t chunk = (tiles + kNumXcd - 1) / kNumXcd;
+        const int64_t x = blockIdx.x % kNumXcd, j = blockIdx.x / kNumXcd;
+        tile = j < chunk ? x * chunk + j : tiles;
+    }
+    if (tile >= tiles) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int dwl_log2 = p.dwl_log2, dwl = 1 << dwl_log2;
+    const int tlane = lane & (dwl - 1);
+    const int team_in_wave = lane >> dwl_log2;
+    const int dim = p.dim;
+
+    // LDS carve-up
+    int *s_wave_cnt = reinterpret_cast<int *>(smem);                     // [16]
+    int *s_last = s_wave_cnt + kMaxWavesPerBlock;                         // [T]
+    int *s_col = s_last + T;                                              // [T*ngs]
+    float *s_w = reinterpret_cast<float *>(s_col + (size_t)T * p.ngs);    // [T*ngs] (WEIGHTED)
+    size_t off_slot = (size_t)(kMaxWavesPerBlock + T + (size_t)T * p.ngs * (WEIGHTED ? 2 : 1)) * 4;
+    off_slot = (off_slot + 15) & ~(size_t)15;
+    float *s_slot = reinterpret_cast<float *>(smem + off_slot);           // [T*dim]
+
+    const int64_t g0 = tile * T;
+    const BlockLayout lay = block_layout(p.ng, g0, num_ng, dwl_log2, s_wave_cnt);
+    const NgEntry e = lay.e;
+
+    // stage the block's contiguous CSR range
+    const int64_t g_last = (g0 + T < num_ng ? g0 + T : num_ng) - 1;
+    const int e0 = p.ng[g0].start;
+    const int e1 = p.ng[g_last].end;
+    for (int i = tid; i < e1 - e0; i += blockDim.x) {
+        s_col[i] = p.colidx[e0 + i];
+        if (WEIGHTED) s_w[i] = p.ew[e0 + i];
+    }
+    for (int i = tid; i < T * dim; i += blockDim.x) s_slot[i] = 0.0f;
+    for (int i = tid; i < T; i += blockDim.x) s_last[i] = 0;
+    __syncthreads();
+    const int slot = block_layout_slot(lay, dwl_log2, s_wave_cnt);
+
+    const int len = lay.valid ? e.end - e.start : 0;
+    const int off = e.start - e0;
+    const bool first = (e.flags & 1) != 0;
+
+    // teams that continue the node of the team before them in the same wave
+    const unsigned long long cont = __ballot(lay.valid && !lay.leader && team_in_wave > 0);
+    const bool seg_head = lay.valid && (team_in_wave == 0 || lay.leader);
+    int lastflag = lay.valid ? (e.flags & 2) : 0;
+    bool lastflag_done = false;
+    bool complete_in_wave = false;
+
+    for (int c0 = 0; c0 < p.iter_total; c0 += ITER) {
+        float acc[ITER][VEC];
+        bool dok[ITER];
+#pragma unroll
+        for (int c = 0; c < ITER; ++c) {
+            dok[c] = ((c0 + c) * dwl + tlane) * VEC < dim;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[c][j] = 0.0f;
+        }
+        const float *xb = p.X + (size_t)(c0 * dwl + tlane) * VEC;
+
+        for (int base = 0; base < len; base += U) {
+            int col[U];
+            float w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = base + u;
+                const bool a = k < len;
+                col[u] = a ? s_col[off + k] : -1;
+                if (WEIGHTED) w[u] = a ? s_w[off + k] : 0.0f;
+            }
+            float v[U][ITER][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int c = 0; c < ITER; ++c) {
+                    if (col[u] >= 0 && dok[c]) {
+                        load_vec<VEC>(v[u][c], xb + (size_t)col[u] * dim + (size_t)c * dwl * VEC);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) v[u][c][j] = 0.0f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < ITER; ++c)
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) {
+                        if (WEIGHTED) acc[c][j] = fmaf(w[u], v[u][c][j], acc[c][j]);
+                        else acc[c][j] += v[u][c][j];
+                    }
+        }
+
+        // segmented reduction over the teams of this wave that share a target node
+        if (cont != 0ull) {
+            const int key = lay.valid ? e.node : -1;
+            for (int o = dwl; o < 64; o <<= 1) {
+                const int okey = __shfl_down(key, o);
+                const bool take = (lane + o < 64) && key >= 0 && okey == key;
+#pragma unroll
+                for (int c = 0; c < ITER; ++c)
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) {
+                        const float ov = __shfl_down(acc[c][j], o);
+                        if (take) acc[c][j] += ov;
+                    }
+                if (!lastflag_done) {
+                    const int ol = __shfl_down(lastflag, o);
+                    if (take) lastflag |= ol;
+                }
+            }
+        }
+        lastflag_done = true;
+        complete_in_wave = seg_head && first && lastflag != 0;
+
+        if (seg_head) {
+            if (complete_in_wave) {
+                // all groups of the node sat in this wave: store from registers
+#pragma unroll
+                for (int c = 0; c < ITER; ++c) {
+                    const int d = ((c0 + c) * dwl + tlane) * VEC;
+                    if (d < dim) {
+                        float r[VEC];
+                        if (SELF) {
+                            float xs[VEC];
+                            load_vec<VEC>(xs, p.X + (size_t)e.node * dim + d);
+#pragma unroll
+                            for (int j = 0; j < VEC; ++j) r[j] = fmaf(p.self_scale, xs[j], acc[c][j]);
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < VEC; ++j) r[j] = acc[c][j];
+                        }
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
+                        store_vec<VEC>(p.out + (size_t)e.node * dim + d, r);
+                    }
+                }
+            } else {
+                // the node continues in another wave (or block): accumulate in its LDS slot
+                float *srow = s_slot + (size_t)slot * dim;
+#pragma unroll
+                for (int c = 0; c < ITER; ++c) {
+                    const int d = ((c0 + c) * dwl + tlane) * VEC;
+                    if (d < dim) {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) atomicAdd(&srow[d + j], acc[c][j]);
+                    }
+                }
+                if (lastflag != 0 && tlane == 0) s_last[slot] = 1;
+            }
+        }
+    }
+    __syncthreads();
+
+    // leader flush (Algorithm 1): one team per slot moves the block's partial row to global memory
+    if (lay.leader && !complete_in_wave) {
+        const bool complete = first && s_last[slot] != 0;
+        const float *srow = s_slot + (size_t)slot * dim;
+        float *orow = p.out + (size_t)e.node * dim;
+        for (int c = 0; c < p.iter_total; ++c) {
+            const int d = (c * dwl + tlane) * VEC;
+            if (d >= dim) break;
+            float r[VEC];
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) r[j] = srow[d + j];
+            if (SELF && first) {
+                float xs[VEC];
+                load_vec<VEC>(xs, p.X + (size_t)e.node * dim + d);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) r[j] = fmaf(p.self_scale, xs[j], r[j]);
+            }
+            if (complete) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
+                store_vec<VEC>(orow + d, r);
+            } else {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) atomicAdd(&orow[d + j], r[j]);
+            }
+        }
+    }
+}
+
+// Ablation of the block-level optimisations: every neighbor group adds its partial row to global
+// memory with atomics; `out` must have been initialised (zero, or the self term) beforehand.
+template <bool WEIGHTED>
+__global__ __launch_bounds__(256) void k_aggregate_noblock(AggParams p)
+{
+    const WsHeader *hdr = p.hdr;
+    if (!header_ok(hdr, p)) return;
+    const int64_t num_ng = hdr->num_ng;
+    const int dwl_log2 = p.dwl_log2, dwl = 1 << dwl_log2;
+    const int lane = threadIdx.x & 63;
+    const int tlane = lane & (dwl - 1);
+    const int64_t team = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> dwl_log2;
+    if (team >= num_ng) return;
+    const NgEntry e = p.ng[team];
+    for (int d = tlane; d < p.dim; d += dwl) {
+        float acc = 0.0f;
+        for (int k = e.start; k < e.end; ++k) {
+            const float x = p.X[(size_t)p.colidx[k] * p.dim + d];
+            acc = WEIGHTED ? fmaf(p.ew[k], x, acc) : acc + x;
+        }
+        atomicAdd(&p.out[(size_t)e.node * p.dim + d], acc);
+    }
+}
+
+// out = SELF ? self_scale * X : 0 for every row (initialisation of the ablation path).
+__global__ __launch_bounds__(256) void k_fill_rows(AggParams p, int self)
+{
+    const int64_t total = (int64_t)p.n * p.dim;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x)
+        p.out[i] = self ? p.self_scale * p.X[i] : 0.0f;
+}
+
+__global__ __launch_bounds__(256) void k_epilogue_all(AggParams p)
+{
+    const int64_t total = (int64_t)p.n * p.dim;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x)
+        p.out[i] = epilogue(p.out[i], p.bias, (int)(i % p.dim), p.relu);
+}
+
+template <int VEC, int ITER, int U>
+static void launch_main(bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s, const AggParams &p)
+{
+    if (self) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, true>), grid, block, lds, s, p);
+    else if (weighted) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, true, false>), grid, block, lds, s, p);
+    else hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, false>), grid, block, lds, s, p);
+}
+
+template <int VEC>
+static void launch_vec(int iter, bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s,
+                       const AggParams &p)
+{
+    // U neighbor rows in flight per lane, sized so that U*ITER*VEC stays near 32 registers
+    constexpr int U1 = 8, U2 = VEC == 4 ? 4 : 8, U3 = 4, U4 = VEC == 4 ? 2 : 4;
+    switch (iter) {
+        case 1: launch_main<VEC, 1, U1>(weighted, self, grid, block, lds, s, p); break;
+        case 2: launch_main<VEC, 2, U2>(weighted, self, grid, block, lds, s, p); break;
+        case 3: launch_main<VEC, 3, U3>(weighted, self, grid, block, lds, s, p); break;
+        default: launch_main<VEC, 4, U4>(weighted, self, grid, block, lds, s, p); break;
+    }
+}
+
+// Shared implementation of gnn_aggregate_gcn / gnn_aggregate_gin and of the aggregation step of
+// gnn_layer_forward.  self: add self_scale * X[i] (GIN).  bias/relu: fused epilogue.
+int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                   const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
+                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes, hipStream_t s)
+{
+    if (n < 0 || nnz < 0 || nnz >= ((int64_t)1 << 31) || dim <= 0 || ngs < 0 || dw < 0 || wpb < 0) return GNN_EINVAL;
+    if (!rowptr || (nnz > 0 && !colidx)) return GNN_EINVAL;
+    if (n > 0 && (!X || !out)) return GNN_EINVAL;
+    if (X == out && n > 0) return GNN_EINVAL;
+    if (dw > 64 || (dw & (dw - 1)) != 0) return GNN_EINVAL;
+    if (wpb > kMaxWavesPerBlock) return GNN_EINVAL;
+    if (n == 0) return GNN_OK;
+
+    // widest vector the row length and the pointers' alignment allow
+    int vec = 1;
+    const uintptr_t al = (uintptr_t)X | (uintptr_t)out;
+    if (dim % 4 == 0 && al % 16 == 0) vec = 4;
+    else if (dim % 2 == 0 && al % 8 == 0) vec = 2;
+
+    decide_defaults(n, nnz, 0, dim, vec, &ngs, &dw, &wpb);
+    int dwl_log2 = 0;
+    while ((1 << dwl_log2) < dw) ++dwl_log2;
+
+    const WsLayout L = ws_layout(n, nnz, 0, ngs);
+    if (!workspace || ((uintptr_t)workspace) % kAlign != 0 || workspace_bytes < L.total) return GNN_EWORKSPACE;
+    char *ws = (char *)workspace;
+
+    if (!(flags & GNN_FLAG_REUSE_PARTITION)) {
+        const int rc = partition_build_impl(n, nnz, rowptr, ngs, workspace, workspace_bytes, s);
+        if (rc != GNN_OK) return rc;
+    }
+
+    AggParams p;
+    p.hdr = (WsHeader *)(ws + L.header);
+    p.ng = (const NgEntry *)(ws + L.ng);
+    p.ngptr = (const int *)(ws + L.ngptr);
+    p.colidx = colidx;
+    p.ew = ew;
+    p.X = X;
+    p.out = out;
+    p.bias = bias;
+    p.self_scale = self_scale;
+    p.relu = relu;
+    p.n = n;
+    p.dim = dim;
+    p.ngs = ngs;
+    p.dwl_log2 = dwl_log2;
+    p.nnz = nnz;
+    p.xcd_remap = (flags & GNN_FLAG_NO_XCD_REMAP) ? 0 : 1;
+    const int units = (dim + vec - 1) / vec;
+    p.iter_total = (units + dw - 1) / dw;
+
+    const int64_t ng_cap = L.ng_capacity;
+    const bool weighted = ew != nullptr;
+
+    if (flags & GNN_FLAG_NO_BLOCK_OPT) {
+        p.T = 1;
+        hipLaunchKernelGGL(k_fill_rows, dim3(2048), dim3(256), 0, s, p, self ? 1 : 0);
+        const int64_t threads = ng_cap << dwl_log2;
+        const int64_t blocks = (threads + 255) / 256;
+        if (blocks > 0) {
+            if (weighted) hipLaunchKernelGGL(k_aggregate_noblock<true>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+            else hipLaunchKernelGGL(k_aggregate_noblock<false>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+        }
+        if (bias || relu) hipLaunchKernelGGL(k_epilogue_all, dim3(2048), dim3(256), 0, s, p);
+        GNN_HIP_TRY(hipGetLastError());
+        return GNN_OK;
+    }
+
+    const int T = wpb * (64 >> dwl_log2);
+    p.T = T;
+    size_t lds = (size_t)(kMaxWavesPerBlock + T + (size_t)T * ngs * (weighted ? 2 : 1)) * 4;
+    lds = (lds + 15) & ~(size_t)15;
+    lds += (size_t)T * dim * 4;
+    if (lds > kMaxLdsBytes) return GNN_ELIMIT;
+
+    const int64_t tiles_upper = (ng_cap + T - 1) / T;
+    int64_t grid = tiles_upper;
+    if (p.xcd_remap) grid = (tiles_upper + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (grid >= ((int64_t)1 << 31)) return GNN_ELIMIT;
+
+    const int64_t init_blocks = ((int64_t)n + 255) / 256;
+    if (self) hipLaunchKernelGGL(k_agg_init<true>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(k_agg_init<false>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+
+    if (grid > 0) {
+        const dim3 g((unsigned)grid), b((unsigned)(wpb * 64));
+        const int iter = p.iter_total < 4 ? p.iter_total : 4;
+        if (vec == 4) launch_vec<4>(iter, weighted, self, g, b, lds, s, p);
+        else if (vec == 2) launch_vec<2>(iter, weighted, self, g, b, lds, s, p);
+        else launch_vec<1>(iter, weighted, self, g, b, lds, s, p);
+    }
+    if (bias || relu) hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+    GNN_HIP_TRY(hipGetLastError());
+    return GNN_OK;
+}
+
+}  // namespace gnn
+
+using namespace gnn;
+
+extern "C" {
+
+int gnn_aggregate_gcn(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *ew,
+                      const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t waves_per_block,
+                      uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return aggregate_impl(false, 0.0f, n, nnz, rowptr, colidx, ew, X, out, dim, ngs, dw, waves_per_block, flags,
+                          nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, float eps,
+                      const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t waves_per_block,
+                      uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return aggregate_impl(true, 1.0f + eps, n, nnz, rowptr, colidx, nullptr, X, out, dim, ngs, dw, waves_per_block,
+                          flags, nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+}  // extern "C"

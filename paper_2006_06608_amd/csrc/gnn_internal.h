@@ -1,0 +1,102 @@
+// Internal declarations shared by the translation units of the library (not installed).
+#ifndef GNN_INTERNAL_H
+#define GNN_INTERNAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "gnn.h"
+
+namespace gnn {
+
+constexpr uint32_t kMagic = 0x474e4e41u;  // "GNNA"
+constexpr int kWaveSize = 64;
+constexpr int kNumXcd = 8;
+constexpr int kMaxWavesPerBlock = 16;
+constexpr size_t kAlign = 256;
+constexpr size_t kMaxLdsBytes = 64 * 1024;  // per block, keeps several blocks per CU inside the 160 KB LDS
+
+// First 256 bytes of the workspace (device memory).  Written by the partition kernels.
+struct WsHeader {
+    uint32_t magic;
+    int32_t n;
+    int64_t nnz;
+    int32_t ngs;
+    int32_t status;  // GNN_OK or the error a kernel recorded
+    int64_t num_ng;  // number of neighbor groups
+    int64_t ng_capacity;
+    uint64_t rowptr_addr;
+};
+
+// One neighbor group (Sec. 4.1): target node, CSR range [start, end), flags.
+// flags bit 0: first group of its node, bit 1: last group of its node.
+struct alignas(16) NgEntry {
+    int32_t node;
+    int32_t start;
+    int32_t end;
+    int32_t flags;
+};
+
+struct WsLayout {
+    size_t header;   // offset of WsHeader
+    size_t ngptr;    // int32[n+1]: id of the first neighbor group of node v; [n] = num_ng
+    size_t scan;     // int32[scan_blocks + 1]
+    size_t ng;       // NgEntry[ng_capacity]
+    size_t tmp;      // float[n * max_dim]
+    size_t total;
+    int64_t ng_capacity;
+    int64_t scan_blocks;
+};
+
+constexpr int kScanTile = 2048;  // nodes per block in the partition scan
+
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Upper bound on the number of neighbor groups: every group holds >= 1 entry, and a row of
+// d entries makes ceil(d/ngs) <= d/ngs + 1 groups.
+inline int64_t ng_upper_bound(int32_t n, int64_t nnz, int32_t ngs)
+{
+    int64_t a = nnz;
+    int64_t b = nnz / (ngs > 0 ? ngs : 1) + (int64_t)n;
+    return a < b ? a : b;
+}
+
+inline WsLayout ws_layout(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs_for_capacity)
+{
+    WsLayout L;
+    L.ng_capacity = ng_upper_bound(n, nnz, ngs_for_capacity > 0 ? ngs_for_capacity : 1);
+    L.scan_blocks = ((int64_t)n + kScanTile - 1) / kScanTile;
+    size_t off = 0;
+    L.header = off;
+    off += align_up(sizeof(WsHeader));
+    L.ngptr = off;
+    off += align_up(sizeof(int32_t) * ((size_t)n + 1));
+    L.scan = off;
+    off += align_up(sizeof(int32_t) * ((size_t)L.scan_blocks + 1));
+    L.ng = off;
+    off += align_up(sizeof(NgEntry) * (size_t)(L.ng_capacity > 0 ? L.ng_capacity : 1));
+    L.tmp = off;
+    off += align_up(sizeof(float) * (size_t)n * (size_t)(max_dim > 0 ? max_dim : 0));
+    L.total = off;
+    return L;
+}
+
+// Host-side record of the last failing HIP status of this thread.
+void set_last_hip_error(int e);
+
+// Model defaults shared by gnn_decide and the entry points (0 = auto).
+void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, int vec, int32_t *ngs,
+                     int32_t *dw, int32_t *wpb);
+
+}  // namespace gnn
+
+#define GNN_HIP_TRY(expr)                                   \
+    do {                                                    \
+        hipError_t e__ = (expr);                            \
+        if (e__ != hipSuccess) {                            \
+            ::gnn::set_last_hip_error((int)e__);            \
+            return GNN_EHIP;                                \
+        }                                                   \
+    } while (0)
+
+#endif

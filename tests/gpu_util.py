@@ -1,0 +1,134 @@
+"""Helpers for the GPU parity tests: device transfer and a runner around the C-ABI binding."""
+import numpy as np
+import torch
+
+import paper_2006_06608_amd as gnn
+
+TOL = 1e-5  # max relative error of the GPU path against the oracle (normwise and guarded componentwise)
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+class DeviceGraph:
+    def __init__(self, rowptr, colidx, ew=None, validate=True):
+        self.n = int(rowptr.size - 1)
+        self.nnz = int(colidx.size)
+        self.rowptr = dev(rowptr.astype(np.int32))
+        self.colidx = dev(colidx.astype(np.int32)) if self.nnz else torch.zeros(1, dtype=torch.int32, device="cuda")
+        self.ew = None if ew is None else (dev(ew.astype(np.float32)) if self.nnz else torch.zeros(1, device="cuda"))
+        if validate:
+            gnn.gnn_validate_csr_device(self.n, self.nnz, self.rowptr, self.colidx)
+
+
+def run_gcn(G, X, ngs=0, dw=0, wpb=0, flags=0, ws=None):
+    Xd = dev(X)
+    out = torch.full_like(Xd, float("nan"))
+    if ws is None:
+        ws = gnn.alloc_workspace(G.n, G.nnz, 0, ngs)
+    gnn.gnn_aggregate_gcn(G.n, G.nnz, G.rowptr, G.colidx, G.ew, Xd, out, X.shape[1], ngs, dw, wpb, flags, ws)
+    torch.cuda.synchronize()
+    gnn.gnn_workspace_status(ws)
+    return out.cpu().numpy()
+
+
+def run_gin(G, eps, X, ngs=0, dw=0, wpb=0, flags=0, ws=None):
+    Xd = dev(X)
+    out = torch.full_like(Xd, float("nan"))
+    if ws is None:
+        ws = gnn.alloc_workspace(G.n, G.nnz, 0, ngs)
+    gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, eps, Xd, out, X.shape[1], ngs, dw, wpb, flags, ws)
+    torch.cuda.synchronize()
+    gnn.gnn_workspace_status(ws)
+    return out.cpu().numpy()
+
+
+class LayerChain:
+    """A multi-layer model run layer by layer through gnn_layer_forward (ReLU after every layer but
+    the last) and checked two ways:
+
+    * per layer, on identical inputs: the oracle's layer is applied to the GPU's own previous
+      output, and the GPU layer must match it within TOL, normwise and componentwise against the
+      layer's error scale (sum of absolute values of all terms of its two operations);
+    * end to end: the GPU's final output against the oracle's own chain, normwise within TOL.
+    """
+
+    def __init__(self, kind, rp, ci, ew, eps, X, Ws, bs=None, ngs=0, dw=0, wpb=0, G=None, name="model"):
+        import oracle
+        self.oracle = oracle
+        self.kind, self.rp, self.ci, self.ew, self.eps = kind, rp, ci, ew, eps
+        self.Ws, self.bs = Ws, bs if bs is not None else [None] * len(Ws)
+        self.ngs, self.dw, self.wpb, self.name = ngs, dw, wpb, name
+        self.G = G if G is not None else DeviceGraph(rp, ci, ew)
+        dims = [X.shape[1]] + [W.shape[1] for W in Ws]
+        self.ws = gnn.alloc_workspace(self.G.n, self.G.nnz, max(dims), ngs)
+        self.gpu = dev(X)      # GPU activations entering the next layer
+        self.ref = X           # the oracle's own chain
+        self.done = 0
+        self.errors = []
+
+    def _oracle_layer(self, H, l, want_abs):
+        relu = l != len(self.Ws) - 1
+        if self.kind == gnn.GNN_GCN:
+            return self.oracle.gcn_layer(self.rp, self.ci, self.ew, H, self.Ws[l], self.bs[l], relu, want_abs=want_abs)
+        return self.oracle.gin_layer(self.rp, self.ci, self.eps, H, self.Ws[l], self.bs[l], relu, want_abs=want_abs)
+
+    def step(self):
+        l = self.done
+        W, b = self.Ws[l], self.bs[l]
+        G = self.G
+        out = torch.full((G.n, W.shape[1]), float("nan"), device="cuda")
+        flags = gnn.GNN_FLAG_REUSE_PARTITION if l > 0 else 0  # the partition depends on (graph, ngs) only
+        gnn.gnn_layer_forward(self.kind, G.n, G.nnz, G.rowptr, G.colidx, G.ew, self.eps, self.gpu, W.shape[0], dev(W),
+                              None if b is None else dev(b), W.shape[1], l != len(self.Ws) - 1, out, self.ngs,
+                              self.dw, self.wpb, flags, self.ws)
+        torch.cuda.synchronize()
+        gnn.gnn_workspace_status(self.ws)
+        gpu_in = self.gpu.cpu().numpy()
+        ref_tf, scale = self._oracle_layer(gpu_in, l, True)
+        got = out.cpu().numpy()
+        self.errors.append(assert_parity(got, ref_tf, scale, f"{self.name} layer {l + 1} (same inputs)"))
+        self.ref = ref_tf if l == 0 else self._oracle_layer(self.ref, l, False)
+        self.gpu = out
+        self.done += 1
+        if self.done == len(self.Ws):
+            from util import parity_errors
+            normwise, _ = parity_errors(got, self.ref, None)
+            assert normwise <= TOL, f"{self.name}: end-to-end normwise error {normwise:.3e} > {TOL}"
+            self.errors.append((normwise, None))
+
+    def run_to(self, layers):
+        while self.done < layers:
+            self.step()
+        return self
+
+    def output(self):
+        return self.gpu.cpu().numpy()
+
+
+def run_model(kind, G, eps, X, Ws, bs=None, ngs=0, dw=0, wpb=0):
+    """Layers chained through gnn_layer_forward without checks; returns the final activations."""
+    dims = [X.shape[1]] + [W.shape[1] for W in Ws]
+    ws = gnn.alloc_workspace(G.n, G.nnz, max(dims), ngs)
+    H = dev(X)
+    flags = 0
+    for l, W in enumerate(Ws):
+        out = torch.full((G.n, W.shape[1]), float("nan"), device="cuda")
+        b = None if bs is None or bs[l] is None else dev(bs[l])
+        gnn.gnn_layer_forward(kind, G.n, G.nnz, G.rowptr, G.colidx, G.ew, eps, H, W.shape[0], dev(W), b, W.shape[1],
+                              l != len(Ws) - 1, out, ngs, dw, wpb, flags, ws)
+        flags = gnn.GNN_FLAG_REUSE_PARTITION
+        H = out
+    torch.cuda.synchronize()
+    gnn.gnn_workspace_status(ws)
+    return H.cpu().numpy()
+
+
+def assert_parity(got, ref, abs_ref, what=""):
+    from util import parity_errors
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    normwise, guarded = parity_errors(got, ref, abs_ref)
+    assert normwise <= TOL, f"{what}: normwise error {normwise:.3e} > {TOL}"
+    assert guarded <= TOL, f"{what}: guarded componentwise error {guarded:.3e} > {TOL}"
+    return normwise, guarded

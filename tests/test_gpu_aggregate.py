@@ -1,0 +1,218 @@
+"""GPU parity tests: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2006_06608_amd as gnn
+from gnn_synth import config_graph, features
+from util import csr_from_edges, random_sym_csr
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import DeviceGraph, assert_parity, dev, run_gcn, run_gin
+
+
+def _graph(kind):
+    if kind == "powerlaw":
+        g = config_graph(2, shrink=4)  # ~4.9k nodes, hubs, self loops
+        return g.rowptr, g.colidx
+    if kind == "batch":
+        g = config_graph(3, shrink=16)
+        return g.rowptr, g.colidx
+    if kind == "rmat":
+        g = config_graph(5, shrink=64)  # 16k nodes, many isolated, skewed
+        return g.rowptr, g.colidx
+    if kind == "star":
+        n = 6001
+        return csr_from_edges(n, [(0, i) for i in range(1, n)], self_loops=True)
+    raise ValueError(kind)
+
+
+# ------------------------------------------------------------------ Sec. 4.1 / Algorithm 1 (bit-exact)
+@pytest.mark.parametrize("kind", ["powerlaw", "batch", "rmat", "star"])
+@pytest.mark.parametrize("ngs", [1, 2, 3, 8, 32])
+def test_partition_matches_oracle(kind, ngs):
+    rp, ci = _graph(kind)
+    G = DeviceGraph(rp, ci)
+    ws = gnn.alloc_workspace(G.n, G.nnz, 0, ngs)
+    gnn.gnn_partition_build(G.n, G.nnz, G.rowptr, ngs, ws)
+    node, start, end = gnn.gnn_partition_export(ws)
+    onode, ostart, oend = oracle.ng_partition(rp, ngs)
+    assert np.array_equal(node, onode) and np.array_equal(start, ostart) and np.array_equal(end, oend)
+    _, num_ng, got_ngs = gnn.gnn_workspace_status(ws)
+    assert num_ng == onode.size and got_ngs == ngs
+
+
+@pytest.mark.parametrize("kind,ngs", [("powerlaw", 2), ("rmat", 4), ("star", 8)])
+@pytest.mark.parametrize("dw,wpb", [(64, 1), (64, 4), (16, 4), (4, 2), (1, 1), (32, 16)])
+def test_block_layout_matches_algorithm1(kind, ngs, dw, wpb):
+    rp, ci = _graph(kind)
+    G = DeviceGraph(rp, ci)
+    ws = gnn.alloc_workspace(G.n, G.nnz, 0, ngs)
+    gnn.gnn_partition_build(G.n, G.nnz, G.rowptr, ngs, ws)
+    dim = 16
+    slot, leader, groups_per_block = gnn.gnn_block_layout_export(ws, dim, dw, wpb)
+    assert groups_per_block == wpb * (64 // dw)
+    onode, _, _ = oracle.ng_partition(rp, ngs)
+    oslot, _, oleader = oracle.alg1_layout(onode, groups_per_block, dim)
+    assert np.array_equal(slot, oslot) and np.array_equal(leader, oleader)
+
+
+# ------------------------------------------------------------------ aggregation parity
+@pytest.mark.parametrize("kind", ["powerlaw", "batch", "rmat", "star"])
+@pytest.mark.parametrize("dim", [16, 64, 96, 3, 22, 7, 130])
+def test_gcn_parity_auto_parameters(kind, dim):
+    rp, ci = _graph(kind)
+    ew = oracle.gcn_norm(rp, ci)
+    X = features(rp.size - 1, dim, seed=dim)
+    ref, ab = oracle.aggregate_gcn(rp, ci, ew, X, want_abs=True)
+    G = DeviceGraph(rp, ci, gnn.gnn_gcn_norm(rp, ci))
+    assert_parity(run_gcn(G, X), ref, ab, f"gcn {kind} dim {dim}")
+
+
+@pytest.mark.parametrize("kind", ["powerlaw", "batch", "rmat", "star"])
+@pytest.mark.parametrize("dim,eps", [(64, 0.0), (16, 0.5), (96, 0.0), (5, -0.25)])
+def test_gin_parity_auto_parameters(kind, dim, eps):
+    rp, ci = _graph(kind)
+    X = features(rp.size - 1, dim, seed=100 + dim)
+    ref, ab = oracle.aggregate_gin(rp, ci, eps, X, want_abs=True)
+    assert_parity(run_gin(DeviceGraph(rp, ci), eps, X), ref, ab, f"gin {kind} dim {dim}")
+
+
+@pytest.mark.parametrize("ngs", [1, 2, 3, 5, 8, 16, 32, 64])
+@pytest.mark.parametrize("dw", [1, 2, 4, 8, 16, 32, 64])
+def test_result_does_not_depend_on_ngs_dw(ngs, dw):
+    rp, ci = _graph("powerlaw")
+    dim = 64
+    X = features(rp.size - 1, dim, seed=7)
+    ew = oracle.gcn_norm(rp, ci)
+    ref, ab = oracle.aggregate_gcn(rp, ci, ew, X, want_abs=True)
+    G = DeviceGraph(rp, ci, ew)
+    wpb = 4 if dw >= 4 else 1
+    assert_parity(run_gcn(G, X, ngs=ngs, dw=dw, wpb=wpb), ref, ab, f"ngs {ngs} dw {dw}")
+
+
+@pytest.mark.parametrize("wpb", [1, 2, 3, 8, 16])
+@pytest.mark.parametrize("kind", ["rmat", "star"])
+def test_result_does_not_depend_on_block_size_or_xcd_order(wpb, kind):
+    rp, ci = _graph(kind)
+    X = features(rp.size - 1, 64, seed=8)
+    ref, ab = oracle.aggregate_gin(rp, ci, 0.0, X, want_abs=True)
+    G = DeviceGraph(rp, ci)
+    assert_parity(run_gin(G, 0.0, X, ngs=4, dw=16, wpb=wpb), ref, ab, f"wpb {wpb}")
+    assert_parity(run_gin(G, 0.0, X, ngs=4, dw=16, wpb=wpb, flags=gnn.GNN_FLAG_NO_XCD_REMAP), ref, ab, "no remap")
+
+
+def test_unit_weights_and_integer_data_are_exact():
+    # sums of small integers are exact in fp32 whatever the order: GPU == oracle bitwise
+    rp, ci = _graph("rmat")
+    rng = np.random.default_rng(3)
+    X = rng.integers(-3, 4, size=(rp.size - 1, 32)).astype(np.float32)
+    G = DeviceGraph(rp, ci)
+    assert np.array_equal(run_gcn(G, X), oracle.aggregate_gcn(rp, ci, None, X))
+    assert np.array_equal(run_gin(G, 1.0, X), oracle.aggregate_gin(rp, ci, 1.0, X))
+    ones = np.ones((rp.size - 1, 16), dtype=np.float32)
+    assert np.array_equal(run_gin(G, 0.0, ones)[:, 0], (1 + np.diff(rp)).astype(np.float32))
+
+
+def test_block_level_ablation_matches_too():
+    rp, ci = _graph("powerlaw")
+    X = features(rp.size - 1, 16, seed=9)
+    ew = oracle.gcn_norm(rp, ci)
+    ref, ab = oracle.aggregate_gcn(rp, ci, ew, X, want_abs=True)
+    assert_parity(run_gcn(DeviceGraph(rp, ci, ew), X, flags=gnn.GNN_FLAG_NO_BLOCK_OPT), ref, ab, "no block opt gcn")
+    ref, ab = oracle.aggregate_gin(rp, ci, 0.25, X, want_abs=True)
+    assert_parity(run_gin(DeviceGraph(rp, ci), 0.25, X, flags=gnn.GNN_FLAG_NO_BLOCK_OPT), ref, ab, "no block opt gin")
+
+
+# ------------------------------------------------------------------ degenerate inputs
+def test_empty_graph_single_node_and_isolated_nodes():
+    X = features(5, 8, seed=1)
+    rp = np.zeros(6, dtype=np.int32)
+    ci = np.zeros(0, dtype=np.int32)
+    G = DeviceGraph(rp, ci, np.zeros(0, np.float32))
+    assert np.array_equal(run_gcn(G, X), np.zeros_like(X))
+    assert np.array_equal(run_gin(DeviceGraph(rp, ci), 1.0, X), 2 * X)
+    # one node with a self loop
+    rp1 = np.array([0, 1], dtype=np.int32)
+    ci1 = np.array([0], dtype=np.int32)
+    x1 = features(1, 16, seed=2)
+    assert np.array_equal(run_gcn(DeviceGraph(rp1, ci1, np.ones(1, np.float32)), x1), x1)
+    # n = 0
+    ws = gnn.alloc_workspace(0, 0)
+    z = torch.zeros(1, device="cuda")
+    gnn.gnn_aggregate_gin(0, 0, dev(np.zeros(1, np.int32)), dev(np.zeros(1, np.int32)), 0.0, z, z.clone(), 4, 0, 0, 0, 0, ws)
+    # isolated nodes scattered between connected ones, last nodes isolated
+    rp2, ci2 = csr_from_edges(70, [(0, 5), (5, 9), (9, 33), (33, 34), (2, 60)])
+    X2 = features(70, 64, seed=3)
+    ref, ab = oracle.aggregate_gin(rp2, ci2, 0.0, X2, want_abs=True)
+    assert_parity(run_gin(DeviceGraph(rp2, ci2), 0.0, X2), ref, ab, "isolated")
+    ref = oracle.aggregate_gcn(rp2, ci2, None, X2)
+    got = run_gcn(DeviceGraph(rp2, ci2), X2)
+    assert np.array_equal(got[np.diff(rp2) == 0], np.zeros((int((np.diff(rp2) == 0).sum()), 64), np.float32))
+    np.testing.assert_allclose(got, ref, rtol=1e-6, atol=1e-6)
+
+
+def test_stale_workspace_and_bad_csr_are_reported():
+    rp, ci = _graph("batch")
+    G = DeviceGraph(rp, ci)
+    X = dev(features(G.n, 16, seed=4))
+    out = torch.zeros_like(X)
+    ws = gnn.alloc_workspace(G.n, G.nnz, 0, 2)
+    ws.zero_()
+    gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, X, out, 16, 4, 0, 0, gnn.GNN_FLAG_REUSE_PARTITION, ws)
+    assert gnn.gnn_workspace_status(ws, check=False)[0] == -6  # GNN_ESTALE
+    gnn.gnn_partition_build(G.n, G.nnz, G.rowptr, 4, ws)
+    gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, X, out, 16, 8, 0, 0, gnn.GNN_FLAG_REUSE_PARTITION, ws)
+    assert gnn.gnn_workspace_status(ws, check=False)[0] == -6  # partition is for another ngs
+    # rowptr[n] != nnz
+    gnn.gnn_partition_build(G.n, G.nnz - 1, G.rowptr, 4, gnn.alloc_workspace(G.n, G.nnz, 0, 1))
+    ws2 = gnn.alloc_workspace(G.n, G.nnz, 0, 1)
+    gnn.gnn_partition_build(G.n, G.nnz - 1, G.rowptr, 4, ws2)
+    assert gnn.gnn_workspace_status(ws2, check=False)[0] == -2  # GNN_ECSR
+    with pytest.raises(gnn.GnnError):
+        gnn.gnn_validate_csr_device(G.n, G.nnz - 1, G.rowptr, G.colidx)
+    bad = G.colidx.clone()
+    bad[5] = G.n
+    with pytest.raises(gnn.GnnError):
+        gnn.gnn_validate_csr_device(G.n, G.nnz, G.rowptr, bad)
+    # too small / missing workspace is caught on the host
+    with pytest.raises(gnn.GnnError):
+        gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, X, out, 16, 4, 0, 0, 0, ws[:256])
+    with pytest.raises(gnn.GnnError):
+        gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, X, out, 16, 4, 3, 0, 0, ws)  # dw not a power of two
+
+
+def test_reuse_partition_gives_identical_results():
+    rp, ci = _graph("rmat")
+    G = DeviceGraph(rp, ci)
+    X = features(G.n, 64, seed=5)
+    ws = gnn.alloc_workspace(G.n, G.nnz, 0, 8)
+    a = run_gin(G, 0.0, X, ngs=8, ws=ws)
+    b = run_gin(G, 0.0, X, ngs=8, flags=gnn.GNN_FLAG_REUSE_PARTITION, ws=ws)
+    ref, ab = oracle.aggregate_gin(rp, ci, 0.0, X, want_abs=True)
+    assert_parity(a, ref, ab, "fresh")
+    assert_parity(b, ref, ab, "reused")
+
+
+def test_renumbered_graph_gives_the_same_aggregation():
+    g = config_graph(4, shrink=32)
+    perm, iperm, _, did = gnn.gnn_reorder(g.rowptr, g.colidx)
+    assert did
+    ew = gnn.gnn_gcn_norm(g.rowptr, g.colidx)
+    rp2, ci2, ew2 = gnn.gnn_apply_perm_csr(g.rowptr, g.colidx, perm, ew)
+    X = features(g.n, 96, seed=6)
+    Xd, Xp = dev(X), torch.empty(g.n, 96, device="cuda")
+    gnn.gnn_permute_rows(g.n, 96, dev(perm), Xd, Xp)
+    assert np.array_equal(Xp.cpu().numpy(), oracle.permute_rows(X, perm))  # bit-exact row gather
+    G2 = DeviceGraph(rp2, ci2, ew2)
+    out_p = dev(run_gcn(G2, Xp.cpu().numpy()))
+    out = torch.empty_like(out_p)
+    gnn.gnn_permute_rows(g.n, 96, dev(iperm), out_p, out)
+    ref, ab = oracle.aggregate_gcn(g.rowptr, g.colidx, oracle.gcn_norm(g.rowptr, g.colidx), X, want_abs=True)
+    assert_parity(out.cpu().numpy(), ref, ab, "renumbered")
+    back = torch.empty_like(Xd)
+    gnn.gnn_permute_rows(g.n, 96, dev(iperm), Xp, back)
+    assert torch.equal(back, Xd)

@@ -1,0 +1,150 @@
+"""GPU parity tests for the Update GEMM, whole layers, and the five configurations at full size."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2006_06608_amd as gnn
+from gnn_synth import BASE_SEED, config_graph, config_spec, features, glorot
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import DeviceGraph, LayerChain, assert_parity, dev, run_gcn, run_gin
+
+
+@pytest.mark.parametrize("n,K,M", [(1, 1, 1), (63, 5, 3), (64, 16, 3), (1000, 500, 16), (777, 96, 16), (4097, 64, 64),
+                                   (300, 16, 22), (129, 33, 70), (200, 700, 40), (50, 1323, 7)])
+@pytest.mark.parametrize("relu,bias", [(False, False), (True, True)])
+def test_update_gemm_parity(n, K, M, relu, bias):
+    rng = np.random.default_rng(n + K + M)
+    A = rng.standard_normal((n, K)).astype(np.float32)
+    W = glorot(K, M, seed=K * 1000 + M)
+    b = rng.standard_normal(M).astype(np.float32) if bias else None
+    ref, ab = oracle.gemm_bias_act(A, W, b, relu, want_abs=True)
+    out = torch.full((n, M), float("nan"), device="cuda")
+    gnn.gnn_update_gemm(n, K, M, dev(A), dev(W), dev(b), relu, out)
+    torch.cuda.synchronize()
+    assert_parity(out.cpu().numpy(), ref, ab, f"gemm {n}x{K}x{M}")
+
+
+def test_update_gemm_identity_is_exact():
+    A = features(500, 64, seed=1)
+    out = torch.empty(500, 64, device="cuda")
+    gnn.gnn_update_gemm(500, 64, 64, dev(A), dev(np.eye(64, dtype=np.float32)), None, False, out)
+    assert np.array_equal(out.cpu().numpy(), A)
+
+
+@pytest.mark.parametrize("kind", ["gcn", "gin"])
+@pytest.mark.parametrize("bias", [False, True])
+def test_layers_with_bias_and_relu(kind, bias):
+    g = config_graph(2 if kind == "gcn" else 5, shrink=4 if kind == "gcn" else 64)
+    rng = np.random.default_rng(11)
+    X = features(g.n, 40, seed=12)
+    Ws = [glorot(40, 24, seed=13), glorot(24, 24, seed=14), glorot(24, 5, seed=15)]
+    bs = [rng.standard_normal(W.shape[1]).astype(np.float32) for W in Ws] if bias else None
+    if kind == "gcn":
+        ew = oracle.gcn_norm(g.rowptr, g.colidx)
+        LayerChain(gnn.GNN_GCN, g.rowptr, g.colidx, ew, 0.0, X, Ws, bs, name="gcn").run_to(3)
+    else:
+        LayerChain(gnn.GNN_GIN, g.rowptr, g.colidx, None, 0.3, X, Ws, bs, name="gin").run_to(3)
+
+
+def _weights(cfg):
+    dims = config_spec(cfg)["dims"]
+    return [glorot(dims[i], dims[i + 1], BASE_SEED + cfg, stream=20 + i) for i in range(len(dims) - 1)]
+
+
+def test_config1_single_gcn_aggregation_full_size():
+    g = config_graph(1)
+    assert (g.n, g.nnz) == (2708, 10556 + 2708)
+    X = features(g.n, 16, BASE_SEED + 1)
+    ew = oracle.gcn_norm(g.rowptr, g.colidx)
+    ref, ab = oracle.aggregate_gcn(g.rowptr, g.colidx, ew, X, want_abs=True)
+    G = DeviceGraph(g.rowptr, g.colidx, gnn.gnn_gcn_norm(g.rowptr, g.colidx))
+    assert_parity(run_gcn(G, X), ref, ab, "config 1")
+
+
+def test_config2_two_layer_gcn_full_size():
+    g = config_graph(2)
+    assert (g.n, g.nnz) == (19717, 88648 + 19717)
+    X = features(g.n, 500, BASE_SEED + 2)
+    ew = gnn.gnn_gcn_norm(g.rowptr, g.colidx)
+    assert ew.tobytes() == oracle.gcn_norm(g.rowptr, g.colidx).tobytes()
+    LayerChain(gnn.GNN_GCN, g.rowptr, g.colidx, ew, 0.0, X, _weights(2), name="config 2").run_to(2)
+
+
+def test_config3_five_layer_gin_full_size():
+    g = config_graph(3)
+    X = features(g.n, 64, BASE_SEED + 3)
+    LayerChain(gnn.GNN_GIN, g.rowptr, g.colidx, None, 0.0, X, _weights(3), name="config 3").run_to(5)
+
+
+# Configurations 4 and 5 take the oracle several seconds per layer: one test per layer, state kept
+# between them (a layer's test first runs whatever earlier layers are still missing).
+_chains = {}
+
+
+def _config4_chain(renumber):
+    key = ("cfg4", renumber)
+    if key not in _chains:
+        g = config_graph(4)
+        assert (g.n, g.nnz) == (410236, 4878874 + 410236)
+        rp, ci = g.rowptr, g.colidx
+        X = features(g.n, 96, BASE_SEED + 4)
+        ew = gnn.gnn_gcn_norm(rp, ci)
+        if renumber:
+            perm, iperm, _, did = gnn.gnn_reorder(rp, ci)
+            assert did
+            assert np.array_equal(perm, oracle.reorder(rp, ci)[0])  # bit-exact renumbering at full size
+            rp, ci, ew = gnn.gnn_apply_perm_csr(rp, ci, perm, ew)
+            orp, oci, oew = oracle.apply_perm_csr(g.rowptr, g.colidx, perm, oracle.gcn_norm(g.rowptr, g.colidx))
+            assert rp.tobytes() == orp.tobytes() and ci.tobytes() == oci.tobytes() and ew.tobytes() == oew.tobytes()
+            Xd = torch.empty(g.n, 96, device="cuda")
+            gnn.gnn_permute_rows(g.n, 96, dev(perm), dev(X), Xd)
+            assert np.array_equal(Xd.cpu().numpy(), oracle.permute_rows(X, perm))
+            X = Xd.cpu().numpy()
+        _chains[key] = (LayerChain(gnn.GNN_GCN, rp, ci, ew, 0.0, X, _weights(4), name=f"config 4 renumber={renumber}"),
+                        rp, ci, ew, X)
+    return _chains[key]
+
+
+@pytest.mark.parametrize("renumber", [False, True])
+def test_config4_aggregation_dim96_full_size(renumber):
+    chain, rp, ci, ew, X = _config4_chain(renumber)
+    ref, ab = oracle.aggregate_gcn(rp, ci, ew, X, want_abs=True)
+    assert_parity(run_gcn(chain.G, X), ref, ab, f"config 4 aggregation renumber={renumber}")
+
+
+@pytest.mark.parametrize("renumber", [False, True])
+@pytest.mark.parametrize("layer", [1, 2])
+def test_config4_two_layer_gcn_full_size(renumber, layer):
+    _config4_chain(renumber)[0].run_to(layer)
+
+
+def _config5_chain(ngs):
+    key = ("cfg5", ngs)
+    if key not in _chains:
+        g = config_graph(5)
+        assert g.n == 1 << 20
+        X = features(g.n, 64, BASE_SEED + 5)
+        _chains[key] = LayerChain(gnn.GNN_GIN, g.rowptr, g.colidx, None, 0.0, X, _weights(5), ngs=ngs,
+                                  name=f"config 5 ngs={ngs}")
+    return _chains[key]
+
+
+@pytest.mark.parametrize("layer", [1, 2, 3, 4, 5])
+def test_config5_five_layer_gin_full_size(layer):
+    _config5_chain(0).run_to(layer)
+
+
+@pytest.mark.parametrize("ngs", [2, 4, 8, 16, 32])
+def test_config5_aggregation_for_every_group_size_of_the_sweep(ngs):
+    chain = _config5_chain(0)
+    g = config_graph(5)
+    X = features(g.n, 64, BASE_SEED + 5)
+    key = ("cfg5", "agg_ref")
+    if key not in _chains:
+        _chains[key] = oracle.aggregate_gin(g.rowptr, g.colidx, 0.0, X, want_abs=True)
+    ref, ab = _chains[key]
+    assert_parity(run_gin(chain.G, 0.0, X, ngs=ngs), ref, ab, f"config 5 aggregation ngs {ngs}")
