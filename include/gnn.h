@@ -13,7 +13,9 @@
  *     prints.  gnn_strerror() names a code; gnn_last_hip_error() gives the HIP status
  *     behind the calling thread's last GNN_EHIP.
  *   - "HOST" / "DEVICE" on a pointer says where the memory must live.  The caller owns
- *     every buffer; the library allocates no device memory and keeps no state between calls.
+ *     every buffer and the library keeps no state between calls.  The compute entry points
+ *     allocate nothing; only the diagnostic calls that copy results to the host
+ *     (gnn_block_layout_export, gnn_validate_csr_device) use a temporary device buffer.
  *   - Matrices are row-major fp32; CSR indices are int32 (nnz < 2^31); n * dim is
  *     addressed in 64 bits.  In and out buffers must not alias.
  *   - DEVICE entry points only enqueue work on `stream` (a hipStream_t, NULL = the null
@@ -53,6 +55,9 @@ extern "C" {
 #define GNN_FLAG_NO_BLOCK_OPT 2u    /* ablation (Sec. 7.4 "block-level optimization"): no scratch-memory
                                        slots, no leaders; every neighbor group adds to global memory */
 #define GNN_FLAG_NO_XCD_REMAP 4u    /* keep the hardware's round-robin block-to-XCD order */
+#define GNN_FLAG_NO_PIPELINE 8u     /* one block per tile instead of persistent, software-pipelined blocks
+                                       (the general kernel, used anyway when a block would serve more
+                                       than 64 groups or a wave more than 512 index entries) */
 
 /* ================================================================================== */
 /* HOST-side preparation                                                              */
@@ -164,6 +169,16 @@ int gnn_layer_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, c
                       const float *b, int32_t out_dim, int relu, float *out, int32_t ngs, int32_t dw,
                       int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
                       void *stream);
+
+/* gnn_layer_forward with two timing taps: ev_agg_start / ev_agg_stop (hipEvent_t, either may be
+ * NULL) are recorded on `stream` immediately before and after the main aggregation kernel of
+ * the layer, so that a benchmark can time that kernel inside a running model without a
+ * profiler.  Everything else is identical to gnn_layer_forward. */
+int gnn_layer_forward_timed(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                            const float *ew, float eps, const float *X, int32_t in_dim, const float *W,
+                            const float *b, int32_t out_dim, int relu, float *out, int32_t ngs, int32_t dw,
+                            int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
+                            void *stream, void *ev_agg_start, void *ev_agg_stop);
 
 /* Row gather for renumbering: Y[perm[i],:] = X[i,:] (pass iperm to undo).  DEVICE pointers,
  * perm int32[n]. */

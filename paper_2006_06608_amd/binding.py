@@ -9,16 +9,16 @@ import numpy as np
 
 __all__ = [
     "GnnError", "lib_path", "load", "exported_symbols",
-    "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_NO_XCD_REMAP",
+    "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_NO_XCD_REMAP", "GNN_FLAG_NO_PIPELINE",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
-    "gnn_update_gemm", "gnn_layer_forward", "gnn_permute_rows", "gnn_strerror", "gnn_version",
-    "alloc_workspace",
+    "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
+    "gnn_version", "alloc_workspace",
 ]
 
 GNN_GCN, GNN_GIN = 0, 1
-GNN_FLAG_REUSE_PARTITION, GNN_FLAG_NO_BLOCK_OPT, GNN_FLAG_NO_XCD_REMAP = 1, 2, 4
+GNN_FLAG_REUSE_PARTITION, GNN_FLAG_NO_BLOCK_OPT, GNN_FLAG_NO_XCD_REMAP, GNN_FLAG_NO_PIPELINE = 1, 2, 4, 8
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libgnn_mi355x.so")
@@ -28,8 +28,8 @@ _SYMBOLS = [
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
-    "gnn_update_gemm", "gnn_layer_forward", "gnn_permute_rows", "gnn_strerror", "gnn_last_hip_error",
-    "gnn_version",
+    "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
+    "gnn_last_hip_error", "gnn_version",
 ]
 
 
@@ -275,6 +275,29 @@ def gnn_layer_forward(kind, n, nnz, rowptr, colidx, ew, eps, X, in_dim, W, b, ou
                                   _dev(out, "float32", "out"), _i32(ngs), _i32(dw), _i32(waves_per_block),
                                   _u32(flags), wp, wb, _stream(stream))
     _check(rc, "gnn_layer_forward")
+
+
+def _event(ev):
+    """hipEvent_t of a recorded-capable torch.cuda.Event (None -> NULL)."""
+    if ev is None:
+        return None
+    if not ev.cuda_event:  # torch creates the handle lazily, on the first record
+        raise ValueError("the event has no handle yet: record it once before passing it")
+    return ctypes.c_void_p(ev.cuda_event)
+
+
+def gnn_layer_forward_timed(kind, n, nnz, rowptr, colidx, ew, eps, X, in_dim, W, b, out_dim, relu, out, ngs=0, dw=0,
+                            waves_per_block=0, flags=0, workspace=None, stream=None, ev_agg_start=None,
+                            ev_agg_stop=None):
+    wp, wb = _ws(workspace)
+    rc = load().gnn_layer_forward_timed(ctypes.c_int(kind), _i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"),
+                                        _dev(colidx, "int32", "colidx"), _dev(ew, "float32", "ew"), _f32(eps),
+                                        _dev(X, "float32", "X"), _i32(in_dim), _dev(W, "float32", "W"),
+                                        _dev(b, "float32", "b"), _i32(out_dim), ctypes.c_int(1 if relu else 0),
+                                        _dev(out, "float32", "out"), _i32(ngs), _i32(dw), _i32(waves_per_block),
+                                        _u32(flags), wp, wb, _stream(stream), _event(ev_agg_start),
+                                        _event(ev_agg_stop))
+    _check(rc, "gnn_layer_forward_timed")
 
 
 def gnn_permute_rows(n, dim, perm, X, Y, stream=None):

@@ -17,72 +17,16 @@
 // without any entry, are initialised by a small kernel that runs first.
 #include <hip/hip_runtime.h>
 
-#include "gnn_device.h"
-#include "gnn_internal.h"
+#include "gnn_agg_common.h"
 
 namespace gnn {
 
 int partition_build_impl(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t ngs, void *workspace,
                          size_t workspace_bytes, hipStream_t s);
-
-struct AggParams {
-    WsHeader *hdr;
-    const NgEntry *ng;
-    const int *ngptr;
-    const int *colidx;
-    const float *ew;
-    const float *X;
-    float *out;
-    const float *bias;  // epilogue: out = act(sum + bias); may be null
-    float self_scale;   // 1 + eps (GIN)
-    int relu;
-    int n;
-    int dim;
-    int ngs;
-    int dwl_log2;
-    int T;           // neighbor groups per block
-    int iter_total;  // chunks of dwl*VEC floats per row
-    int xcd_remap;
-    int64_t nnz;
-};
-
-template <int VEC>
-__device__ __forceinline__ void load_vec(float (&r)[VEC], const float *p)
-{
-    if constexpr (VEC == 4) {
-        const float4 v = *reinterpret_cast<const float4 *>(p);
-        r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
-    } else if constexpr (VEC == 2) {
-        const float2 v = *reinterpret_cast<const float2 *>(p);
-        r[0] = v.x; r[1] = v.y;
-    } else {
-        r[0] = *p;
-    }
-}
-
-template <int VEC>
-__device__ __forceinline__ void store_vec(float *p, const float (&r)[VEC])
-{
-    if constexpr (VEC == 4) {
-        *reinterpret_cast<float4 *>(p) = make_float4(r[0], r[1], r[2], r[3]);
-    } else if constexpr (VEC == 2) {
-        *reinterpret_cast<float2 *>(p) = make_float2(r[0], r[1]);
-    } else {
-        *p = r[0];
-    }
-}
-
-__device__ __forceinline__ bool header_ok(const WsHeader *hdr, const AggParams &p)
-{
-    return hdr->magic == kMagic && hdr->status == GNN_OK && hdr->ngs == p.ngs && hdr->n == p.n && hdr->nnz == p.nnz;
-}
-
-__device__ __forceinline__ float epilogue(float v, const float *bias, int d, int relu)
-{
-    if (bias) v += bias[d];
-    if (relu) v = fmaxf(v, 0.0f);
-    return v;
-}
+size_t pipe_lds_bytes(int T, int dim, int ngs, int dwl_log2, int wpb, bool weighted);
+int pipe_blocks(int vec, int iter, bool weighted, bool self, int cus, int wpb, size_t lds, int64_t tiles_upper, int n);
+int launch_aggregate_pipe(int vec, int iter, bool weighted, bool self, int blocks, int wpb, size_t lds, hipStream_t s,
+                          AggParams &p);
 
 // Rows the main kernel will not store plainly: rows without entries get their final value, rows
 // whose groups span several blocks are zeroed for the atomic adds.  One wave scans 64 nodes.
@@ -112,7 +56,7 @@ __global__ __launch_bounds__(256) void k_agg_init(AggParams p)
     int action = 0;
     if (v < p.n) {
         const int c0 = p.ngptr[v], c1 = p.ngptr[v + 1];
-        if (c1 == c0) action = 2;
+        if (c1 == c0) action = p.do_empty ? 0 : 2;
         else if (c0 / p.T != (c1 - 1) / p.T) action = 1;
     }
     unsigned long long m = __ballot(action != 0);
@@ -418,7 +362,8 @@ static void launch_vec(int iter, bool weighted, bool self, dim3 grid, dim3 block
 // gnn_layer_forward.  self: add self_scale * X[i] (GIN).  bias/relu: fused epilogue.
 int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
                    const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
-                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes, hipStream_t s)
+                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes, hipStream_t s,
+                   hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (n < 0 || nnz < 0 || nnz >= ((int64_t)1 << 31) || dim <= 0 || ngs < 0 || dw < 0 || wpb < 0) return GNN_EINVAL;
     if (!rowptr || (nnz > 0 && !colidx)) return GNN_EINVAL;
@@ -428,11 +373,7 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     if (wpb > kMaxWavesPerBlock) return GNN_EINVAL;
     if (n == 0) return GNN_OK;
 
-    // widest vector the row length and the pointers' alignment allow
-    int vec = 1;
-    const uintptr_t al = (uintptr_t)X | (uintptr_t)out;
-    if (dim % 4 == 0 && al % 16 == 0) vec = 4;
-    else if (dim % 2 == 0 && al % 8 == 0) vec = 2;
+    const int vec = pick_vec(dim, X, out);
 
     decide_defaults(n, nnz, 0, dim, vec, &ngs, &dw, &wpb);
     int dwl_log2 = 0;
@@ -464,6 +405,7 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     p.dwl_log2 = dwl_log2;
     p.nnz = nnz;
     p.xcd_remap = (flags & GNN_FLAG_NO_XCD_REMAP) ? 0 : 1;
+    p.do_empty = 0;
     const int units = (dim + vec - 1) / vec;
     p.iter_total = (units + dw - 1) / dw;
 
@@ -492,21 +434,47 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     if (lds > kMaxLdsBytes) return GNN_ELIMIT;
 
     const int64_t tiles_upper = (ng_cap + T - 1) / T;
+    const int64_t init_blocks = ((int64_t)n + 255) / 256;
+    const int iter = p.iter_total < 4 ? p.iter_total : 4;
+
+    // persistent, pipelined kernel whenever its requirements hold
+    const size_t plds = (flags & GNN_FLAG_NO_PIPELINE) ? 0 : pipe_lds_bytes(T, dim, ngs, dwl_log2, wpb, weighted);
+    if (plds > 0 && plds <= kMaxLdsBytes) {
+        int dev = 0, cus = 0;
+        GNN_HIP_TRY(hipGetDevice(&dev));
+        GNN_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        const int blocks = pipe_blocks(vec, iter, weighted, self, cus, wpb, plds, tiles_upper, n);
+        if (blocks < 0) return blocks;
+        if (blocks > 0) {
+            p.do_empty = 1;
+            if (self) hipLaunchKernelGGL(k_agg_init<true>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+            else hipLaunchKernelGGL(k_agg_init<false>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+            if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
+            const int rc = launch_aggregate_pipe(vec, iter, weighted, self, blocks, wpb, plds, s, p);
+            if (rc != GNN_OK) return rc;
+            if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
+            if (bias || relu)
+                hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+            GNN_HIP_TRY(hipGetLastError());
+            return GNN_OK;
+        }
+    }
+
     int64_t grid = tiles_upper;
     if (p.xcd_remap) grid = (tiles_upper + kNumXcd - 1) / kNumXcd * kNumXcd;
     if (grid >= ((int64_t)1 << 31)) return GNN_ELIMIT;
 
-    const int64_t init_blocks = ((int64_t)n + 255) / 256;
     if (self) hipLaunchKernelGGL(k_agg_init<true>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
     else hipLaunchKernelGGL(k_agg_init<false>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
 
+    if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
     if (grid > 0) {
         const dim3 g((unsigned)grid), b((unsigned)(wpb * 64));
-        const int iter = p.iter_total < 4 ? p.iter_total : 4;
         if (vec == 4) launch_vec<4>(iter, weighted, self, g, b, lds, s, p);
         else if (vec == 2) launch_vec<2>(iter, weighted, self, g, b, lds, s, p);
         else launch_vec<1>(iter, weighted, self, g, b, lds, s, p);
     }
+    if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
     if (bias || relu) hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
     GNN_HIP_TRY(hipGetLastError());
     return GNN_OK;
@@ -523,7 +491,7 @@ int gnn_aggregate_gcn(int32_t n, int64_t nnz, const int32_t *rowptr, const int32
                       uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
 {
     return aggregate_impl(false, 0.0f, n, nnz, rowptr, colidx, ew, X, out, dim, ngs, dw, waves_per_block, flags,
-                          nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream);
+                          nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream, nullptr, nullptr);
 }
 
 int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, float eps,
@@ -531,7 +499,7 @@ int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32
                       uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
 {
     return aggregate_impl(true, 1.0f + eps, n, nnz, rowptr, colidx, nullptr, X, out, dim, ngs, dw, waves_per_block,
-                          flags, nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream);
+                          flags, nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream, nullptr, nullptr);
 }
 
 }  // extern "C"

@@ -174,13 +174,24 @@ void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, in
         }
         *dw = d;
     }
-    // neighbor-group size from the mean row length: short rows want small groups (few idle
-    // slots in the last group of a row), long rows want enough loads in flight per lane.
+    // neighbor-group size, from the graph alone so that one partition serves every layer of a
+    // model.  Time ~ (#groups * per-group cost) + (#entries * per-row cost): bigger groups mean
+    // fewer tuples, reductions and flushes per entry, and a team needs at least the 8 rows it keeps
+    // in flight; past about twice the mean row length most groups are a whole row and nothing
+    // more is gained.  Measured knee on MI355X: 16..32, as the paper found on its GPUs (Sec. 7.4).
     if (*ngs <= 0) {
         const double avg = n > 0 ? (double)nnz / (double)n : 0.0;
-        *ngs = avg < 6.0 ? 4 : (avg < 24.0 ? 8 : 16);
+        int g = 8;
+        while (g < 32 && (double)g < 2.0 * avg) g *= 2;
+        *ngs = g;
     }
-    if (*wpb <= 0) *wpb = 4;
+    // waves per block: 4 (the paper's preferred small blocks, Sec. 6), fewer when a wave already
+    // carries many teams, so that a block serves at most 64 neighbor groups
+    if (*wpb <= 0) {
+        const int teams = 64 / (*dw > 0 ? *dw : 1);
+        int w = 64 / teams;
+        *wpb = w < 1 ? 1 : (w > 4 ? 4 : w);
+    }
 }
 
 }  // namespace gnn

@@ -84,6 +84,15 @@ inline WsLayout ws_layout(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs_f
 // Host-side record of the last failing HIP status of this thread.
 void set_last_hip_error(int e);
 
+// Widest per-lane vector (floats) that the row length and the two pointers' alignment allow.
+inline int pick_vec(int32_t dim, const void *a, const void *b)
+{
+    const uintptr_t al = (uintptr_t)a | (uintptr_t)b;
+    if (dim % 4 == 0 && al % 16 == 0) return 4;
+    if (dim % 2 == 0 && al % 8 == 0) return 2;
+    return 1;
+}
+
 // Model defaults shared by gnn_decide and the entry points (0 = auto).
 void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, int vec, int32_t *ngs,
                      int32_t *dw, int32_t *wpb);

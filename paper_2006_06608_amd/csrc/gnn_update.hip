@@ -14,7 +14,8 @@ namespace gnn {
 
 int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
                    const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
-                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes, hipStream_t s);
+                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes, hipStream_t s,
+                   hipEvent_t ev_start, hipEvent_t ev_stop);
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -231,11 +232,13 @@ int gnn_permute_rows(int32_t n, int32_t dim, const int32_t *perm, const float *X
     return GNN_OK;
 }
 
-int gnn_layer_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *ew,
-                      float eps, const float *X, int32_t in_dim, const float *W, const float *b, int32_t out_dim,
-                      int relu, float *out, int32_t ngs, int32_t dw, int32_t waves_per_block, uint32_t flags,
-                      void *workspace, size_t workspace_bytes, void *stream)
+int gnn_layer_forward_timed(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                            const float *ew, float eps, const float *X, int32_t in_dim, const float *W, const float *b,
+                            int32_t out_dim, int relu, float *out, int32_t ngs, int32_t dw, int32_t waves_per_block,
+                            uint32_t flags, void *workspace, size_t workspace_bytes, void *stream, void *ev_agg_start,
+                            void *ev_agg_stop)
 {
+    hipEvent_t ev0 = (hipEvent_t)ev_agg_start, ev1 = (hipEvent_t)ev_agg_stop;
     if (kind != GNN_GCN && kind != GNN_GIN) return GNN_EINVAL;
     if (n < 0 || nnz < 0 || nnz >= ((int64_t)1 << 31) || in_dim <= 0 || out_dim <= 0 || ngs < 0) return GNN_EINVAL;
     if (n == 0) return GNN_OK;
@@ -243,13 +246,11 @@ int gnn_layer_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, c
     hipStream_t s = (hipStream_t)stream;
     const int32_t agg_dim = kind == GNN_GCN ? out_dim : in_dim;
     // the partition's capacity (and with it the offset of the intermediate) depends on ngs: resolve
-    // the automatic choice here exactly as the aggregation will
-    int32_t ngs_r = ngs, dw_r = dw > 0 ? dw : 0, wpb_r = waves_per_block;
-    {
-        int32_t dw_tmp = 1;
-        decide_defaults(n, nnz, 0, agg_dim, 1, &ngs_r, &dw_tmp, &wpb_r);
-    }
-    (void)dw_r;
+    // the automatic choice here exactly as the aggregation will.  The intermediate sits at a
+    // 256-byte aligned offset, so only the caller's pointer can narrow the vector width.
+    int32_t ngs_r = ngs, dw_r = dw, wpb_r = waves_per_block;
+    decide_defaults(n, nnz, 0, agg_dim, pick_vec(agg_dim, kind == GNN_GCN ? (const void *)out : (const void *)X, nullptr),
+                    &ngs_r, &dw_r, &wpb_r);
     const WsLayout L = ws_layout(n, nnz, agg_dim, ngs_r);
     if (!workspace || ((uintptr_t)workspace) % kAlign != 0 || workspace_bytes < L.total) return GNN_EWORKSPACE;
     float *tmp = (float *)((char *)workspace + L.tmp);
@@ -258,12 +259,21 @@ int gnn_layer_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, c
         int rc = update_gemm_impl(n, in_dim, out_dim, X, W, nullptr, 0, tmp, s);
         if (rc != GNN_OK) return rc;
         return aggregate_impl(false, 0.0f, n, nnz, rowptr, colidx, ew, tmp, out, out_dim, ngs_r, dw, waves_per_block,
-                              flags, b, relu, workspace, workspace_bytes, s);
+                              flags, b, relu, workspace, workspace_bytes, s, ev0, ev1);
     }
     int rc = aggregate_impl(true, 1.0f + eps, n, nnz, rowptr, colidx, nullptr, X, tmp, in_dim, ngs_r, dw,
-                            waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, s);
+                            waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, s, ev0, ev1);
     if (rc != GNN_OK) return rc;
     return update_gemm_impl(n, in_dim, out_dim, tmp, W, b, relu, out, s);
+}
+
+int gnn_layer_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *ew,
+                      float eps, const float *X, int32_t in_dim, const float *W, const float *b, int32_t out_dim,
+                      int relu, float *out, int32_t ngs, int32_t dw, int32_t waves_per_block, uint32_t flags,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gnn_layer_forward_timed(kind, n, nnz, rowptr, colidx, ew, eps, X, in_dim, W, b, out_dim, relu, out, ngs, dw,
+                                   waves_per_block, flags, workspace, workspace_bytes, stream, nullptr, nullptr);
 }
 
 }  // extern "C"
