@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--dw", type=int, default=0)
     ap.add_argument("--wpb", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy, the known-size kernel against which the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -106,6 +109,13 @@ def main():
             H = out
         return H
 
+    if args.calibrate_copy:
+        ca = torch.empty(1 << 26, dtype=torch.float32, device="cuda")
+        cb = torch.empty_like(ca)
+        cb.copy_(ca)
+        torch.cuda.synchronize()
+        del ca, cb
+
     for _ in range(args.warmup):
         step(-1)
     torch.cuda.synchronize()
@@ -154,7 +164,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"cfg{cfg}: {spec['desc']}; n={n}, directed edges={nnz}, {layers} layers",
                    "ngs": ngs, "dw": dw, "waves_per_block": wpb, "neighbor_groups": num_ng},
-        "roofline": {"bound": "hbm", "kernel": "k_aggregate_pipe<4,1,8,false,true> (GIN, Dim 64)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": ("k_aggregate_pipe" if ngs <= 8 else "k_aggregate") + "<4,1,8,false,true> (GIN, Dim 64)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, ngs)),
                      "algorithmic_bytes_per_launch": agg_bytes, "avg_kernel_ms": agg_ms},

@@ -28,6 +28,9 @@ struct AggParams {
     int iter_total;  // chunks of dwl*VEC floats per row
     int xcd_remap;
     int do_empty;    // 1: the main kernel writes the rows without entries; 0: the init kernel does
+    int stream_out;  // 1: write output rows with streaming stores
+    int extra_blocks;  // one-block-per-tile kernel: blocks appended to the grid for the rows without entries
+    int64_t tile_blocks;  // one-block-per-tile kernel: blocks that serve tiles
     int64_t nnz;
 };
 
@@ -57,6 +60,46 @@ __device__ __forceinline__ void store_vec(float *p, const float (&r)[VEC])
     }
 }
 
+#ifndef GNN_NT_STORE
+#define GNN_NT_STORE 1
+#endif
+#ifndef GNN_NT_INDEX
+#define GNN_NT_INDEX 1
+#endif
+
+// Output rows are written once and not read again by the kernel: a streaming (non-temporal) store
+// keeps them from displacing neighbour rows in the caches.
+template <int VEC>
+__device__ __forceinline__ void store_vec_stream(float *p, const float (&r)[VEC])
+{
+#if GNN_NT_STORE
+    typedef float v4 __attribute__((ext_vector_type(4)));
+    typedef float v2 __attribute__((ext_vector_type(2)));
+    if constexpr (VEC == 4) {
+        v4 v = {r[0], r[1], r[2], r[3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<v4 *>(p));
+    } else if constexpr (VEC == 2) {
+        v2 v = {r[0], r[1]};
+        __builtin_nontemporal_store(v, reinterpret_cast<v2 *>(p));
+    } else {
+        __builtin_nontemporal_store(r[0], p);
+    }
+#else
+    store_vec<VEC>(p, r);
+#endif
+}
+
+// Column indices, edge weights and group tuples are read exactly once.
+template <typename T>
+__device__ __forceinline__ T load_stream(const T *p)
+{
+#if GNN_NT_INDEX
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+
 __device__ __forceinline__ bool header_ok(const WsHeader *hdr, const AggParams &p)
 {
     return hdr->magic == kMagic && hdr->status == GNN_OK && hdr->ngs == p.ngs && hdr->n == p.n && hdr->nnz == p.nnz;
@@ -67,6 +110,63 @@ __device__ __forceinline__ float epilogue(float v, const float *bias, int d, int
     if (bias) v += bias[d];
     if (relu) v = fmaxf(v, 0.0f);
     return v;
+}
+
+// Rows without any entry: out = act((1+eps) x + b) (GIN) or act(b).  The calling wave scans chunks
+// of 64 nodes (first_chunk, first_chunk + chunk_stride, ...), lists the empty ones in `mylist`
+// (64 ints of LDS private to the wave) and lets its teams write them side by side, four rows per
+// team in flight.
+template <int VEC, bool SELF>
+__device__ __forceinline__ void write_empty_rows(const AggParams &p, int64_t first_chunk, int64_t chunk_stride,
+                                                 int *mylist)
+{
+    const int lane = threadIdx.x & 63;
+    const int dwl = 1 << p.dwl_log2, G = 64 >> p.dwl_log2;
+    const int tlane = lane & (dwl - 1), team_in_wave = lane >> p.dwl_log2;
+    const int dim = p.dim;
+    const int64_t nchunks = ((int64_t)p.n + 63) / 64;
+    for (int64_t c = first_chunk; c < nchunks; c += chunk_stride) {
+        const int64_t v = c * 64 + lane;
+        const bool empty = v < p.n && p.ngptr[v] == p.ngptr[v + 1];
+        const unsigned long long m = __ballot(empty);
+        if (m == 0ull) continue;
+        const int cnt = __popcll(m);
+        if (empty) mylist[__popcll(m & ((1ull << lane) - 1ull))] = lane;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (int k0 = team_in_wave; k0 < cnt; k0 += 4 * G) {
+            int64_t node[4];
+            bool ok[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int k = k0 + q * G;
+                ok[q] = k < cnt;
+                node[q] = c * 64 + (ok[q] ? mylist[k] : 0);
+            }
+            for (int cc = 0; cc < p.iter_total; ++cc) {
+                const int d = (cc * dwl + tlane) * VEC;
+                if (d >= dim) break;
+                float r[4][VEC];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) r[q][j] = 0.0f;
+                    if (SELF && ok[q]) load_vec<VEC>(r[q], p.X + (size_t)node[q] * dim + d);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (ok[q]) {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j)
+                            r[q][j] = epilogue(SELF ? p.self_scale * r[q][j] : 0.0f, p.bias, d + j, p.relu);
+                        if (p.stream_out) store_vec_stream<VEC>(p.out + (size_t)node[q] * dim + d, r[q]);
+                        else store_vec<VEC>(p.out + (size_t)node[q] * dim + d, r[q]);
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 }  // namespace gnn

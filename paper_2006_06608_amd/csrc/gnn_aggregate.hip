@@ -99,6 +99,11 @@ __global__ __launch_bounds__(256) void k_agg_epilogue_spanning(AggParams p)
     }
 }
 
+#ifndef GNN_XCD_RUN
+#define GNN_XCD_RUN 128
+#endif
+constexpr int kXcdRun = GNN_XCD_RUN;  // consecutive tiles that stay on one XCD
+
 template <int VEC, int ITER, int U, bool WEIGHTED, bool SELF>
 __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 {
@@ -107,15 +112,26 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
     if (!header_ok(hdr, p)) return;
 
     const int T = p.T;
+    if ((int64_t)blockIdx.x >= p.tile_blocks) {
+        // blocks appended to the grid: rows without entries (independent of every tile)
+        const int nw = blockDim.x >> 6, wv = threadIdx.x >> 6;
+        size_t off = (size_t)(kMaxWavesPerBlock + T + (size_t)T * p.ngs * (WEIGHTED ? 2 : 1)) * 4;
+        off = ((off + 15) & ~(size_t)15) + (size_t)T * p.dim * 4;
+        int *s_list = reinterpret_cast<int *>(smem + off);
+        const int64_t eb = (int64_t)blockIdx.x - p.tile_blocks;
+        write_empty_rows<VEC, SELF>(p, eb * nw + wv, (int64_t)p.extra_blocks * nw, s_list + wv * 64);
+        return;
+    }
     const int64_t num_ng = hdr->num_ng;
     const int64_t tiles = (num_ng + T - 1) / T;
     int64_t tile = blockIdx.x;
     if (p.xcd_remap) {
-        // consecutive tiles (neighbouring node ids, hence shared neighbours after renumbering) go to
-        // the same XCD and its L2, instead of being dealt round-robin over the eight XCDs
-        const int64_t chunk = (tiles + kNumXcd - 1) / kNumXcd;
-        const int64_t x = blockIdx.x % kNumXcd, j = blockIdx.x / kNumXcd;
-        tile = j < chunk ? x * chunk + j : tiles;
+        // Blocks are dealt to the eight XCDs round-robin by index.  Give every XCD runs of kXcdRun
+        // consecutive tiles (neighbouring node ids, hence shared neighbours after renumbering, meet
+        // in one L2) while the runs themselves still interleave over the XCDs, which keeps the
+        // load balanced.
+        const int64_t x = blockIdx.x % kNumXcd, q = blockIdx.x / kNumXcd;
+        tile = ((q / kXcdRun) * kNumXcd + x) * kXcdRun + q % kXcdRun;
     }
     if (tile >= tiles) return;
 
@@ -143,8 +159,8 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
     const int e0 = p.ng[g0].start;
     const int e1 = p.ng[g_last].end;
     for (int i = tid; i < e1 - e0; i += blockDim.x) {
-        s_col[i] = p.colidx[e0 + i];
-        if (WEIGHTED) s_w[i] = p.ew[e0 + i];
+        s_col[i] = load_stream(&p.colidx[e0 + i]);
+        if (WEIGHTED) s_w[i] = load_stream(&p.ew[e0 + i]);
     }
     for (int i = tid; i < T * dim; i += blockDim.x) s_slot[i] = 0.0f;
     for (int i = tid; i < T; i += blockDim.x) s_last[i] = 0;
@@ -248,7 +264,8 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
                         }
 #pragma unroll
                         for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
-                        store_vec<VEC>(p.out + (size_t)e.node * dim + d, r);
+                        if (p.stream_out) store_vec_stream<VEC>(p.out + (size_t)e.node * dim + d, r);
+                        else store_vec<VEC>(p.out + (size_t)e.node * dim + d, r);
                     }
                 }
             } else {
@@ -288,7 +305,8 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
             if (complete) {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
-                store_vec<VEC>(orow + d, r);
+                if (p.stream_out) store_vec_stream<VEC>(orow + d, r);
+                else store_vec<VEC>(orow + d, r);
             } else {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) atomicAdd(&orow[d + j], r[j]);
@@ -404,8 +422,13 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     p.ngs = ngs;
     p.dwl_log2 = dwl_log2;
     p.nnz = nnz;
-    p.xcd_remap = (flags & GNN_FLAG_NO_XCD_REMAP) ? 0 : 1;
+    p.xcd_remap = (flags & GNN_FLAG_XCD_RUNS) ? 1 : 0;
     p.do_empty = 0;
+    // streaming stores only for rows made of whole 128-byte lines: shorter rows share a line with
+    // their neighbours and are better merged in L2
+    p.stream_out = (dim % 32 == 0) ? 1 : 0;
+    p.tile_blocks = 0;
+    p.extra_blocks = 0;
     const int units = (dim + vec - 1) / vec;
     p.iter_total = (units + dw - 1) / dw;
 
@@ -431,6 +454,7 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     size_t lds = (size_t)(kMaxWavesPerBlock + T + (size_t)T * ngs * (weighted ? 2 : 1)) * 4;
     lds = (lds + 15) & ~(size_t)15;
     lds += (size_t)T * dim * 4;
+    lds += (size_t)wpb * 64 * 4;  // per-wave list of empty rows (appended blocks)
     if (lds > kMaxLdsBytes) return GNN_ELIMIT;
 
     const int64_t tiles_upper = (ng_cap + T - 1) / T;
@@ -438,7 +462,8 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     const int iter = p.iter_total < 4 ? p.iter_total : 4;
 
     // persistent, pipelined kernel whenever its requirements hold
-    const size_t plds = (flags & GNN_FLAG_NO_PIPELINE) ? 0 : pipe_lds_bytes(T, dim, ngs, dwl_log2, wpb, weighted);
+    const bool want_pipe = !(flags & GNN_FLAG_NO_PIPELINE) && ((flags & GNN_FLAG_PIPELINE) || ngs <= 8);
+    const size_t plds = want_pipe ? pipe_lds_bytes(T, dim, ngs, dwl_log2, wpb, weighted) : 0;
     if (plds > 0 && plds <= kMaxLdsBytes) {
         int dev = 0, cus = 0;
         GNN_HIP_TRY(hipGetDevice(&dev));
@@ -461,15 +486,22 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     }
 
     int64_t grid = tiles_upper;
-    if (p.xcd_remap) grid = (tiles_upper + kNumXcd - 1) / kNumXcd * kNumXcd;
-    if (grid >= ((int64_t)1 << 31)) return GNN_ELIMIT;
+    if (p.xcd_remap) grid = (tiles_upper + kNumXcd * kXcdRun - 1) / (kNumXcd * kXcdRun) * (kNumXcd * kXcdRun);
+    // rows without entries: blocks appended to the grid, each wave taking about four 64-node chunks
+    const int64_t nchunks = ((int64_t)n + 63) / 64;
+    int64_t extra = (nchunks + (int64_t)wpb * 4 - 1) / ((int64_t)wpb * 4);
+    if (extra > 8192) extra = 8192;
+    p.do_empty = 1;
+    p.tile_blocks = grid;
+    p.extra_blocks = (int)extra;
+    if (grid + extra >= ((int64_t)1 << 31)) return GNN_ELIMIT;
 
     if (self) hipLaunchKernelGGL(k_agg_init<true>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
     else hipLaunchKernelGGL(k_agg_init<false>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
 
     if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
-    if (grid > 0) {
-        const dim3 g((unsigned)grid), b((unsigned)(wpb * 64));
+    {
+        const dim3 g((unsigned)(grid + extra)), b((unsigned)(wpb * 64));
         if (vec == 4) launch_vec<4>(iter, weighted, self, g, b, lds, s, p);
         else if (vec == 2) launch_vec<2>(iter, weighted, self, g, b, lds, s, p);
         else launch_vec<1>(iter, weighted, self, g, b, lds, s, p);

@@ -114,8 +114,8 @@ __global__ __launch_bounds__(1024) void k_aggregate_pipe(AggParams p)
             cpre[r] = 0;
             wpre[r] = 0.0f;
             if (k < V.ws1 - V.ws0) {
-                cpre[r] = p.colidx[V.ws0 + k];
-                if (WEIGHTED) wpre[r] = p.ew[V.ws0 + k];
+                cpre[r] = load_stream(&p.colidx[V.ws0 + k]);
+                if (WEIGHTED) wpre[r] = load_stream(&p.ew[V.ws0 + k]);
             }
         }
     };
@@ -247,7 +247,8 @@ __global__ __launch_bounds__(1024) void k_aggregate_pipe(AggParams p)
                             }
 #pragma unroll
                             for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
-                            store_vec<VEC>(p.out + (size_t)e.node * dim + d, r);
+                            if (p.stream_out) store_vec_stream<VEC>(p.out + (size_t)e.node * dim + d, r);
+                            else store_vec<VEC>(p.out + (size_t)e.node * dim + d, r);
                         }
                     }
                 } else {
@@ -289,7 +290,8 @@ __global__ __launch_bounds__(1024) void k_aggregate_pipe(AggParams p)
                 if (complete) {
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
-                    store_vec<VEC>(orow + d, r);
+                    if (p.stream_out) store_vec_stream<VEC>(orow + d, r);
+                    else store_vec<VEC>(orow + d, r);
                 } else {
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) atomicAdd(&orow[d + j], r[j]);
@@ -306,53 +308,8 @@ __global__ __launch_bounds__(1024) void k_aggregate_pipe(AggParams p)
         tl_next = tl_after;
     }
 
-    // rows without any entry: out = act((1+eps) x + b) or act(b).  Every wave scans 64 nodes at a
-    // time and its teams write the empty ones side by side.
-    if (!p.do_empty) return;
-    int *mylist = s_list + wave * 64;
-    const int64_t nchunks = ((int64_t)p.n + 63) / 64;
-    for (int64_t c = b * nwaves + wave; c < nchunks; c += B * nwaves) {
-        const int64_t v = c * 64 + lane;
-        const bool empty = v < p.n && p.ngptr[v] == p.ngptr[v + 1];
-        const unsigned long long m = __ballot(empty);
-        if (m == 0ull) continue;
-        const int cnt = __popcll(m);
-        if (empty) mylist[__popcll(m & ((1ull << lane) - 1ull))] = lane;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        // four rows per team in flight
-        for (int k0 = team_in_wave; k0 < cnt; k0 += 4 * G) {
-            int64_t node[4];
-            bool ok[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int k = k0 + q * G;
-                ok[q] = k < cnt;
-                node[q] = c * 64 + (ok[q] ? mylist[k] : 0);
-            }
-            for (int cc = 0; cc < p.iter_total; ++cc) {
-                const int d = (cc * dwl + tlane) * VEC;
-                if (d >= dim) break;
-                float r[4][VEC];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) r[q][j] = 0.0f;
-                    if (SELF && ok[q]) load_vec<VEC>(r[q], p.X + (size_t)node[q] * dim + d);
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (ok[q]) {
-#pragma unroll
-                        for (int j = 0; j < VEC; ++j)
-                            r[q][j] = epilogue(SELF ? p.self_scale * r[q][j] : 0.0f, p.bias, d + j, p.relu);
-                        store_vec<VEC>(p.out + (size_t)node[q] * dim + d, r[q]);
-                    }
-                }
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-    }
+    // rows without any entry
+    if (p.do_empty) write_empty_rows<VEC, SELF>(p, b * nwaves + wave, B * nwaves, s_list + wave * 64);
 }
 
 template <int VEC, int ITER, int U>
