@@ -1,10 +1,14 @@
 #!/usr/bin/env python3
 """Benchmark of the aggregation hot path on one MI355X.
 
-A step is one forward pass of the 5-layer GIN of configuration 5 (R-MAT scale 20, hidden 64):
-per layer one aggregation (Eq. 3) and one Update GEMM (+ReLU), all through the C-ABI library,
-inputs resident in HBM.  One-time preparation (neighbor partitioning, Sec. 4.1) is done before
-the timed region and reported separately, as the paper does.  Prints ONE JSON line.
+Default workload (the headline): configuration 5, one forward pass of the 5-layer GIN (hidden 64)
+on the R-MAT scale-20 graph: per layer one aggregation (Eq. 3) and one Update GEMM (+ReLU), all
+through the C-ABI library, inputs resident in HBM.  One-time preparation (renumbering, CSR
+relabelling, neighbor partitioning: Sec. 4.1 / 5.1) happens before the timed region and is
+reported separately, as the paper does.  Prints ONE JSON line on stdout.
+
+Other configurations (--config 1..4) are for the tables in the design doc; --ngs/--dw/--wpb/--flags give
+the parameter sweeps, --renumber applies gnn_reorder first.
 """
 from __future__ import annotations
 
@@ -20,9 +24,17 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
-# HBM bytes per aggregation launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
-# profiles/), keyed by (config, ngs); None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+# Bytes that crossed the L2 <-> fabric boundary (Infinity Cache + HBM) per aggregation launch,
+# from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this command, scaled by what the same
+# counters read for a plain 256 MiB copy (FETCH_SIZE x2.0, WRITE_SIZE x1.0 on this machine);
+# summaries under profiles/.  Keyed by (config, ngs, renumber).
+MEASURED_TRAFFIC_BYTES = {
+    (5, 32, False): 3.112e9,  # k_aggregate<4,1,8,false,true>, Dim 64
+    (5, 32, True): 2.940e9,
+    (4, 32, False): 0.475e9,  # k_aggregate<4,1,8,true,false>, Dim 16 (layer 1 of the 2-layer GCN)
+    (4, 32, True): 0.287e9,
+    (3, 8, False): 0.043e9,
+}
 
 
 def log(*a):
@@ -34,10 +46,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=5, choices=[3, 5])
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--ngs", type=int, default=0)
     ap.add_argument("--dw", type=int, default=0)
     ap.add_argument("--wpb", type=int, default=0)
+    ap.add_argument("--flags", type=int, default=0, help="extra GNN_FLAG_* bits for the aggregation")
+    ap.add_argument("--renumber", action="store_true", help="apply gnn_reorder (forced) before the run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, the known-size kernel against which the "
@@ -57,57 +71,65 @@ def main():
     torch.cuda.set_device(0)
     cfg = args.config
     spec = config_spec(cfg)
+    kind = "gin" if spec["kind"] == "gin" else "gcn"
     t0 = time.time()
     g = config_graph(cfg)
+    rp_h, ci_h = g.rowptr, g.colidx
     n, nnz = g.n, g.nnz
     dims = spec["dims"]
-    dim = dims[0]
-    layers = len(dims) - 1
-    X = features(n, dim, BASE_SEED + cfg)
+    layers = len(dims) - 1  # 0 for configuration 1 (a single aggregation)
+    X = features(n, dims[0], BASE_SEED + cfg)
     Ws = [glorot(dims[i], dims[i + 1], BASE_SEED + cfg, stream=20 + i) for i in range(layers)]
     log(f"generated config {cfg}: n={n} nnz={nnz} in {time.time() - t0:.1f}s")
 
+    prep = {}
+    _, aes0 = gnn.gnn_aes(rp_h, ci_h)
+    prep["aes"] = aes0
+    ew_h = None
+    if kind == "gcn":
+        t0 = time.perf_counter()
+        ew_h = gnn.gnn_gcn_norm(rp_h, ci_h)
+        prep["gcn_norm_host_ms"] = (time.perf_counter() - t0) * 1e3
+    perm = None
+    if args.renumber:
+        t0 = time.perf_counter()
+        perm, iperm, _, _ = gnn.gnn_reorder(rp_h, ci_h, force=True)
+        prep["reorder_host_ms"] = (time.perf_counter() - t0) * 1e3
+        t0 = time.perf_counter()
+        if ew_h is None:
+            rp_h, ci_h = gnn.gnn_apply_perm_csr(rp_h, ci_h, perm)
+        else:
+            rp_h, ci_h, ew_h = gnn.gnn_apply_perm_csr(rp_h, ci_h, perm, ew_h)
+        prep["relabel_host_ms"] = (time.perf_counter() - t0) * 1e3
+        prep["aes_after"] = gnn.gnn_aes(rp_h, ci_h)[1]
+
     d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    rp, ci = d(g.rowptr), d(g.colidx)
+    rp, ci = d(rp_h), d(ci_h)
+    ew = None if ew_h is None else d(ew_h)
     Xd = d(X)
+    if args.renumber:  # rows of X move with their nodes (device gather, part of the preparation)
+        Xp = torch.empty_like(Xd)
+        gnn.gnn_permute_rows(n, dims[0], d(perm), Xd, Xp)
+        Xd = Xp
     Wd = [d(W) for W in Ws]
     gnn.gnn_validate_csr_device(n, nnz, rp, ci)
 
-    ngs, dw, wpb = gnn.gnn_decide(n, nnz, 0, dim)
+    agg_dim = dims[0] if (kind == "gin" or layers == 0) else dims[1]
+    ngs, dw, wpb = gnn.gnn_decide(n, nnz, 0, agg_dim)
     ngs = args.ngs or ngs
-    dw = args.dw or dw
-    wpb = args.wpb or wpb
     ws = gnn.alloc_workspace(n, nnz, max(dims), ngs)
     stream = torch.cuda.current_stream()
+    REUSE = gnn.GNN_FLAG_REUSE_PARTITION | args.flags
+    KIND = gnn.GNN_GIN if kind == "gin" else gnn.GNN_GCN
 
-    # one-time preparation, timed on its own
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     gnn.gnn_partition_build(n, nnz, rp, ngs, ws)
     e1.record()
     torch.cuda.synchronize()
-    prep_ms = e0.elapsed_time(e1)
+    prep["partition_ms"] = e0.elapsed_time(e1)
     _, num_ng, _ = gnn.gnn_workspace_status(ws)
-
-    bufs = [torch.empty(n, dim, device="cuda"), torch.empty(n, dim, device="cuda")]
-    nev = layers * args.steps
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nev)]
-    for a, b in evs:  # give every event its handle
-        a.record()
-        b.record()
-    torch.cuda.synchronize()
-
-    def step(k):
-        H = Xd
-        for l in range(layers):
-            out = bufs[l & 1]
-            ea, eb = evs[k * layers + l] if k >= 0 else (None, None)
-            gnn.gnn_layer_forward_timed(gnn.GNN_GIN, n, nnz, rp, ci, None, 0.0, H, dims[l], Wd[l], None, dims[l + 1],
-                                        l != layers - 1, out, ngs, dw, wpb, gnn.GNN_FLAG_REUSE_PARTITION, ws, stream,
-                                        ea, eb)
-            H = out
-        return H
 
     if args.calibrate_copy:
         ca = torch.empty(1 << 26, dtype=torch.float32, device="cuda")
@@ -115,6 +137,50 @@ def main():
         cb.copy_(ca)
         torch.cuda.synchronize()
         del ca, cb
+
+    # ---- the headline aggregation of the configuration, timed alone over the same number of steps
+    # (Dim 64 GIN for configs 3/5, Dim 96 GCN for config 4, Dim 16 GCN for configs 1/2)
+    head_dim = dims[0] if (kind == "gin" or cfg in (1, 4)) else dims[1]
+    Xh = Xd if head_dim == dims[0] else torch.randn(n, head_dim, device="cuda")
+    outh = torch.empty(n, head_dim, device="cuda")
+
+    def head():
+        if kind == "gin":
+            gnn.gnn_aggregate_gin(n, nnz, rp, ci, 0.0, Xh, outh, head_dim, ngs, args.dw, args.wpb, REUSE, ws)
+        else:
+            gnn.gnn_aggregate_gcn(n, nnz, rp, ci, ew, Xh, outh, head_dim, ngs, args.dw, args.wpb, REUSE, ws)
+
+    for _ in range(args.warmup):
+        head()
+    torch.cuda.synchronize()
+    ha, hb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ha.record()
+    for _ in range(args.steps):
+        head()
+    hb.record()
+    torch.cuda.synchronize()
+    head_call_ms = ha.elapsed_time(hb) / args.steps
+
+    # ---- the step: the configuration's model forward (configuration 1: the single aggregation)
+    nlay = max(layers, 1)
+    bufs = [torch.empty(n, max(dims), device="cuda") for _ in range(2)]
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nlay * args.steps)]
+    for a, b in evs:  # torch creates an event's handle on its first record
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+
+    def step(k):
+        if layers == 0:
+            head()
+            return
+        H = Xd
+        for l in range(layers):
+            out = bufs[l & 1].view(-1)[: n * dims[l + 1]].view(n, dims[l + 1])
+            ea, eb = evs[k * layers + l] if k >= 0 else (None, None)
+            gnn.gnn_layer_forward_timed(KIND, n, nnz, rp, ci, ew, 0.0, H, dims[l], Wd[l], None, dims[l + 1],
+                                        l != layers - 1, out, ngs, args.dw, args.wpb, REUSE, ws, stream, ea, eb)
+            H = out
 
     for _ in range(args.warmup):
         step(-1)
@@ -126,31 +192,55 @@ def main():
     t1 = time.perf_counter()
     gnn.gnn_workspace_status(ws)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    agg_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
 
-    # algorithmic bytes of one aggregation launch (the kernel also writes the rows without
-    # neighbours): per edge one neighbour row + its column index; per node its output row and, for
-    # GIN, its own input row, plus its two group-offset words; per neighbor group its 16-byte tuple
-    agg_bytes = nnz * (4 * dim + 4) + n * (4 * dim + 4 * dim + 4) + num_ng * 16
-    achieved = agg_bytes / (agg_ms * 1e-3) / 1e9
-    edges_dim = float(nnz) * dim
-    value = layers * edges_dim / (ms_per_step * 1e-3)
+    # dominant kernel: the aggregation at the model's widest aggregated dimension (layer 1)
+    if layers > 0:
+        per_layer = np.array([[a.elapsed_time(b) for a, b in evs[k * layers:(k + 1) * layers]] for k in range(args.steps)])
+        agg_ms_layers = per_layer.mean(axis=0)
+        dom_dim = agg_dim
+        dom_ms = float(agg_ms_layers[0]) if kind == "gcn" else float(agg_ms_layers.mean())
+    else:
+        agg_ms_layers = np.array([head_call_ms])
+        dom_dim, dom_ms = head_dim, head_call_ms
+
+    def algorithmic_bytes(dim):
+        # per edge one neighbour row + its column index (+ its weight for GCN); per node its output row
+        # (+ its own input row for GIN) and its group-offset word; per neighbor group its 16-byte tuple
+        per_edge = 4 * dim + 4 + (4 if kind == "gcn" else 0)
+        per_node = 4 * dim + 4 + (4 * dim if kind == "gin" else 0)
+        return nnz * per_edge + n * per_node + num_ng * 16
+
+    dom_bytes = algorithmic_bytes(dom_dim)
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    agg_dims = ([dims[0]] * layers if kind == "gin" else dims[1:]) if layers else [head_dim]
+    edges_dim_step = float(nnz) * float(sum(agg_dims))
+    value = edges_dim_step / (ms_per_step * 1e-3)
 
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        sample_layers = 2 if cfg == 5 else layers
-        H = X
         t0 = time.perf_counter()
-        for l in range(sample_layers):
-            H = oracle.gin_layer(g.rowptr, g.colidx, 0.0, H, Ws[l], None, relu=True)
+        if layers == 0:
+            oracle.aggregate_gcn(rp_h, ci_h, ew_h, X)
+            done_dims, sample = [head_dim], "the single aggregation"
+        else:
+            sample_layers = min(layers, 2) if cfg == 5 else layers
+            H = X if perm is None else oracle.permute_rows(X, perm)
+            for l in range(sample_layers):
+                if kind == "gin":
+                    H = oracle.gin_layer(rp_h, ci_h, 0.0, H, Ws[l], None, relu=True)
+                else:
+                    H = oracle.gcn_layer(rp_h, ci_h, ew_h, H, Ws[l], None, relu=True)
+            done_dims = agg_dims[:sample_layers]
+            sample = f"layers 1-{sample_layers} of {layers} on the full graph"
         dt = time.perf_counter() - t0
-        cpu = {"value": sample_layers * edges_dim / dt, "unit": "edge*dim/s", "cores": 1, "kind": "oracle",
-               "sample": f"layers 1-{sample_layers} of {layers} on the full graph ({dt:.1f} s)",
-               "ms_per_layer": dt * 1e3 / sample_layers}
+        cpu = {"value": float(nnz) * sum(done_dims) / dt, "unit": "edge*dim/s", "cores": 1, "kind": "oracle",
+               "sample": f"{sample} ({dt:.1f} s)"}
 
+    # the pipelined kernel is chosen for small groups when every resident block gets several tiles
+    kname = "k_aggregate" if (ngs > 8 and not args.flags & 16) or args.flags & 8 else "k_aggregate_pipe|k_aggregate"
     rec = {
-        "metric": "aggregation edges*dim/s (5-layer GIN forward, whole step incl. Update GEMMs)",
+        "metric": "aggregation edges*dim/s over one model forward (aggregations + Update GEMMs)",
         "value": value,
         "unit": "edge*dim/s",
         "n_gpus": 1,
@@ -162,16 +252,21 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"cfg{cfg}: {spec['desc']}; n={n}, directed edges={nnz}, {layers} layers",
-                   "ngs": ngs, "dw": dw, "waves_per_block": wpb, "neighbor_groups": num_ng},
-        "roofline": {"bound": "hbm", "kernel": ("k_aggregate_pipe" if ngs <= 8 else "k_aggregate") + "<4,1,8,false,true> (GIN, Dim 64)", "achieved": achieved,
+        "config": {"workload": f"cfg{cfg}: {spec['desc']}; n={n}, directed entries={nnz}, layers={layers}",
+                   "ngs": ngs, "dw": args.dw or dw, "waves_per_block": args.wpb or wpb, "neighbor_groups": num_ng,
+                   "renumbered": bool(args.renumber), "flags": args.flags},
+        "roofline": {"bound": "hbm", "kernel": f"{kname} ({kind.upper()}, Dim {dom_dim})", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, ngs)),
-                     "algorithmic_bytes_per_launch": agg_bytes, "avg_kernel_ms": agg_ms},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, ngs, bool(args.renumber))),
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_kernel_ms": dom_ms},
         "cpu_baseline": cpu,
-        "aggregation_only_edges_dim_per_s": edges_dim / (agg_ms * 1e-3),
-        "layer_ms": ms_per_step / layers,
-        "prep_partition_ms": prep_ms,
+        "aggregation_kernel_ms_per_layer": [float(x) for x in agg_ms_layers],
+        "aggregation_only_edges_dim_per_s": float(nnz) * dom_dim / (dom_ms * 1e-3),
+        "layer_ms": ms_per_step / nlay,
+        "headline_aggregation": {"dim": head_dim, "call_ms": head_call_ms,
+                                 "edges_dim_per_s": float(nnz) * head_dim / (head_call_ms * 1e-3),
+                                 "algorithmic_GBps": algorithmic_bytes(head_dim) / (head_call_ms * 1e-3) / 1e9},
+        "prep": prep,
     }
     print(json.dumps(rec), flush=True)
 
