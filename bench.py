@@ -7,7 +7,7 @@ through the C-ABI library, inputs resident in HBM.  One-time preparation (renumb
 relabelling, neighbor partitioning: Sec. 4.1 / 5.1) happens before the timed region and is
 reported separately, as the paper does.  Prints ONE JSON line on stdout.
 
-Other configurations (--config 1..4) are for the tables in the design doc; --ngs/--dw/--wpb/--flags give
+Other configurations (--config 1..4) run the remaining workloads; --ngs/--dw/--wpb/--flags give
 the parameter sweeps, --renumber applies gnn_reorder first.
 """
 from __future__ import annotations
@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--wpb", type=int, default=0)
     ap.add_argument("--flags", type=int, default=0, help="extra GNN_FLAG_* bits for the aggregation")
     ap.add_argument("--renumber", action="store_true", help="apply gnn_reorder (forced) before the run")
+    ap.add_argument("--hidden", type=int, default=0, help="override the hidden dimension of the model (sweep)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step in a HIP graph and time replays (launch-bound small configurations)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, the known-size kernel against which the "
@@ -76,7 +79,9 @@ def main():
     g = config_graph(cfg)
     rp_h, ci_h = g.rowptr, g.colidx
     n, nnz = g.n, g.nnz
-    dims = spec["dims"]
+    dims = list(spec["dims"])
+    if args.hidden and len(dims) > 2:
+        dims = [dims[0]] + [args.hidden] * (len(dims) - 2) + [dims[-1]]
     layers = len(dims) - 1  # 0 for configuration 1 (a single aggregation)
     X = features(n, dims[0], BASE_SEED + cfg)
     Ws = [glorot(dims[i], dims[i + 1], BASE_SEED + cfg, stream=20 + i) for i in range(layers)]
@@ -118,7 +123,6 @@ def main():
     ngs, dw, wpb = gnn.gnn_decide(n, nnz, 0, agg_dim)
     ngs = args.ngs or ngs
     ws = gnn.alloc_workspace(n, nnz, max(dims), ngs)
-    stream = torch.cuda.current_stream()
     REUSE = gnn.GNN_FLAG_REUSE_PARTITION | args.flags
     KIND = gnn.GNN_GIN if kind == "gin" else gnn.GNN_GCN
 
@@ -146,9 +150,11 @@ def main():
 
     def head():
         if kind == "gin":
-            gnn.gnn_aggregate_gin(n, nnz, rp, ci, 0.0, Xh, outh, head_dim, ngs, args.dw, args.wpb, REUSE, ws)
+            gnn.gnn_aggregate_gin(n, nnz, rp, ci, 0.0, Xh, outh, head_dim, ngs, args.dw, args.wpb, REUSE, ws,
+                                  torch.cuda.current_stream())
         else:
-            gnn.gnn_aggregate_gcn(n, nnz, rp, ci, ew, Xh, outh, head_dim, ngs, args.dw, args.wpb, REUSE, ws)
+            gnn.gnn_aggregate_gcn(n, nnz, rp, ci, ew, Xh, outh, head_dim, ngs, args.dw, args.wpb, REUSE, ws,
+                                  torch.cuda.current_stream())
 
     for _ in range(args.warmup):
         head()
@@ -179,12 +185,39 @@ def main():
             out = bufs[l & 1].view(-1)[: n * dims[l + 1]].view(n, dims[l + 1])
             ea, eb = evs[k * layers + l] if k >= 0 else (None, None)
             gnn.gnn_layer_forward_timed(KIND, n, nnz, rp, ci, ew, 0.0, H, dims[l], Wd[l], None, dims[l + 1],
-                                        l != layers - 1, out, ngs, args.dw, args.wpb, REUSE, ws, stream, ea, eb)
+                                        l != layers - 1, out, ngs, args.dw, args.wpb, REUSE, ws,
+                                        torch.cuda.current_stream(), ea, eb)
             H = out
 
     for _ in range(args.warmup):
         step(-1)
     torch.cuda.synchronize()
+    graph_ms = None
+    if args.graph:
+        # the library only enqueues kernels (no memset nodes, no synchronisation), so a step can be
+        # captured; replays are checked against the eager result
+        eager = None
+        if layers:
+            step(-1)
+            torch.cuda.synchronize()
+            eager = bufs[(layers - 1) & 1].view(-1)[: n * dims[-1]].clone()
+        cg = torch.cuda.CUDAGraph()
+        cap_stream = torch.cuda.Stream()
+        with torch.cuda.graph(cg, stream=cap_stream):
+            step(-1)
+        for _ in range(args.warmup):
+            cg.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for _ in range(args.steps):
+            cg.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - tg) * 1e3 / args.steps
+        if eager is not None:
+            # rows finished by float atomics may differ in their last bits from run to run
+            replay = bufs[(layers - 1) & 1].view(-1)[: n * dims[-1]]
+            err = (replay - eager).abs().max().item() / max(eager.abs().max().item(), 1e-30)
+            assert err <= 1e-5, f"graph replay differs from eager by {err:.3e}"
     t0 = time.perf_counter()
     for k in range(args.steps):
         step(k)
@@ -267,6 +300,8 @@ def main():
                                  "edges_dim_per_s": float(nnz) * head_dim / (head_call_ms * 1e-3),
                                  "algorithmic_GBps": algorithmic_bytes(head_dim) / (head_call_ms * 1e-3) / 1e9},
         "prep": prep,
+        "dims": dims,
+        "graph_replay_ms_per_step": graph_ms,
     }
     print(json.dumps(rec), flush=True)
 
