@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--hidden", type=int, default=0, help="override the hidden dimension of the model (sweep)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step in a HIP graph and time replays (launch-bound small configurations)")
+    ap.add_argument("--train", action="store_true",
+                    help="also time a training step (forward + gnn_layer_backward of every layer, no optimizer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, the known-size kernel against which the "
@@ -249,6 +251,44 @@ def main():
     edges_dim_step = float(nnz) * float(sum(agg_dims))
     value = edges_dim_step / (ms_per_step * 1e-3)
 
+    train_ms = None
+    if args.train and layers > 0:
+        # every configuration's graph is symmetric (GCN weights too), so it is its own transpose and
+        # the forward partition serves the backward aggregation
+        bws = torch.empty(max(gnn.gnn_backward_workspace_bytes(n, nnz, dims[l], dims[l + 1], ngs) for l in range(layers)),
+                          dtype=torch.uint8, device="cuda")
+        gnn.gnn_partition_build(n, nnz, rp, ngs, bws)
+        Hs = [Xd] + [torch.empty(n, dims[l + 1], device="cuda") for l in range(layers)]
+        As = [torch.empty(n, dims[l], device="cuda") for l in range(layers)] if kind == "gin" else None
+        dHs = [torch.empty(n, dims[l], device="cuda") for l in range(layers)] + [torch.randn(n, dims[-1], device="cuda")]
+        dWs = [torch.empty(dims[l], dims[l + 1], device="cuda") for l in range(layers)]
+
+        def train_step():
+            for l in range(layers):
+                relu = l != layers - 1
+                if kind == "gin":
+                    gnn.gnn_aggregate_gin(n, nnz, rp, ci, 0.0, Hs[l], As[l], dims[l], ngs, args.dw, args.wpb, REUSE, ws)
+                    gnn.gnn_update_gemm(n, dims[l], dims[l + 1], As[l], Wd[l], None, relu, Hs[l + 1])
+                else:
+                    gnn.gnn_layer_forward(KIND, n, nnz, rp, ci, ew, 0.0, Hs[l], dims[l], Wd[l], None, dims[l + 1], relu,
+                                          Hs[l + 1], ngs, args.dw, args.wpb, REUSE, ws)
+            for l in reversed(range(layers)):
+                relu = l != layers - 1
+                P = As[l] if kind == "gin" else Hs[l]
+                gnn.gnn_layer_backward(KIND, n, nnz, rp, ci, ew, 0.0, P, dims[l], Wd[l], dims[l + 1], relu, Hs[l + 1],
+                                       dHs[l + 1], dHs[l] if l > 0 else None, dWs[l], None, ngs, args.dw, args.wpb,
+                                       REUSE, bws)
+
+        for _ in range(args.warmup):
+            train_step()
+        torch.cuda.synchronize()
+        tt = time.perf_counter()
+        for _ in range(args.steps):
+            train_step()
+        torch.cuda.synchronize()
+        train_ms = (time.perf_counter() - tt) * 1e3 / args.steps
+        gnn.gnn_workspace_status(bws)
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -302,6 +342,7 @@ def main():
         "prep": prep,
         "dims": dims,
         "graph_replay_ms_per_step": graph_ms,
+        "train_step_ms": train_ms,
     }
     print(json.dumps(rec), flush=True)
 

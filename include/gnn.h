@@ -90,6 +90,11 @@ int gnn_gcn_norm(int32_t n, const int32_t *rowptr, const int32_t *colidx, float 
 int gnn_apply_perm_csr(int32_t n, const int32_t *rowptr, const int32_t *colidx, const float *val,
                        const int32_t *perm, int32_t *rowptr2, int32_t *colidx2, float *val2);
 
+/* Transpose of a CSR: entry (i, j, v) becomes (j, i, v); rows of the result sorted by column.  val /
+ * val_t may both be NULL.  HOST pointers, outputs caller-owned with the input's sizes. */
+int gnn_csr_transpose(int32_t n, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                      int32_t *rowptr_t, int32_t *colidx_t, float *val_t);
+
 /* The parameter model re-derived for 256 CUs / 64-lane wavefronts / 160 KB LDS (Sec. 6).
  * Pure host function.  max_degree may be 0 (unknown).  Outputs: ngs (neighbor-group size),
  * dw (lanes that share one neighbor row), waves_per_block. */
@@ -184,6 +189,24 @@ int gnn_layer_forward_timed(int kind, int32_t n, int64_t nnz, const int32_t *row
                             const float *b, int32_t out_dim, int relu, float *out, int32_t ngs, int32_t dw,
                             int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
                             void *stream, void *ev_agg_start, void *ev_agg_stop);
+
+/* Backward pass of gnn_layer_forward (training; the aggregation kernel is reused on gradients,
+ * Sec. 7.2).  rowptr_t / colidx_t / ew_t: the TRANSPOSED graph (gnn_csr_transpose; a symmetric graph
+ * with symmetric weights is its own transpose), and `workspace` holds ITS partition.
+ *   kind GNN_GCN: forward was Y = act(A_hat (X W) + b);  P = X float[n*in_dim].
+ *                 dW = X^T (A_hat^T dZ),  dX = (A_hat^T dZ) W^T,  dZ = dY masked by Y > 0 when relu.
+ *   kind GNN_GIN: forward was Y = act(A W + b), A = (1+eps) X + sum_N X;  P = A float[n*in_dim]
+ *                 (the caller keeps A from gnn_aggregate_gin).  dW = A^T dZ,  dX = (1+eps) dA + sum over
+ *                 the transposed graph of dA,  dA = dZ W^T.
+ * Y (forward output, needed only when relu), dY: float[n*out_dim].  Outputs: dW float[in_dim*out_dim],
+ * db float[out_dim] or NULL, dX float[n*in_dim] or NULL (first layer).  Workspace of
+ * gnn_backward_workspace_bytes().  DEVICE pointers; only enqueues. */
+size_t gnn_backward_workspace_bytes(int32_t n, int64_t nnz, int32_t in_dim, int32_t out_dim, int32_t ngs);
+int gnn_layer_backward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr_t, const int32_t *colidx_t,
+                       const float *ew_t, float eps, const float *P, int32_t in_dim, const float *W,
+                       int32_t out_dim, int relu, const float *Y, const float *dY, float *dX, float *dW,
+                       float *db, int32_t ngs, int32_t dw, int32_t waves_per_block, uint32_t flags,
+                       void *workspace, size_t workspace_bytes, void *stream);
 
 /* Row gather for renumbering: Y[perm[i],:] = X[i,:] (pass iperm to undo).  DEVICE pointers,
  * perm int32[n]. */

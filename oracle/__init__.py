@@ -250,3 +250,62 @@ def gin_model(rowptr, colidx, eps, X, Ws: Sequence[np.ndarray], bs: Optional[Seq
         else:
             H = gin_layer(rowptr, colidx, eps, H, W, b, relu=not last)
     return (H, ab) if want_abs else H
+
+
+# ------------------------------------------------------------------ backward pass (training)
+# Gradients of the layers above, by the chain rule, each product accumulated in double and stored
+# as float between operations (as the forward pass does).  The aggregation of gradients runs over
+# the transposed graph: d/dX of (A X) applied to G is A^T G.
+def csr_transpose(rowptr, colidx, val=None):
+    """Entry (i, j, v) -> (j, i, v); rows of the result sorted by column (stable counting order)."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    n = rowptr.size - 1
+    rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
+    order = np.argsort(colidx, kind="stable")  # ties keep ascending row order
+    rp_t = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(colidx, minlength=n), out=rp_t[1:])
+    ci_t = rows[order].astype(np.int32)
+    if val is None:
+        return rp_t.astype(np.int32), ci_t
+    return rp_t.astype(np.int32), ci_t, _f32(val)[order]
+
+
+def _mm64(A, B):
+    return (np.asarray(A, dtype=np.float64) @ np.asarray(B, dtype=np.float64))
+
+
+def gcn_layer_backward(rowptr, colidx, ew, X, W, relu, Y, dY, want_abs: bool = False):
+    """Forward Y = act(A_hat (X W) + b).  Returns dX, dW, db (and their error scales)."""
+    X, W, dY = _f32(X), _f32(W), _f32(dY)
+    dZ = np.where(_f32(Y) > 0, dY, np.float32(0)) if relu else dY
+    db = dZ.astype(np.float64).sum(axis=0).astype(np.float32)
+    rp_t, ci_t, ew_t = csr_transpose(rowptr, colidx, _f32(ew))
+    dH, dH_abs = aggregate_gcn(rp_t, ci_t, ew_t, dZ, want_abs=True)
+    dW = _mm64(X.T, dH).astype(np.float32)
+    dX = _mm64(dH, W.T).astype(np.float32)
+    if not want_abs:
+        return dX, dW, db
+    s_dW = _mm64(np.abs(X).T, dH_abs)
+    s_dX = _mm64(dH_abs, np.abs(W).T)
+    s_db = np.abs(dZ).astype(np.float64).sum(axis=0)
+    return (dX, dW, db), (s_dX, s_dW, s_db)
+
+
+def gin_layer_backward(rowptr, colidx, eps, A, W, relu, Y, dY, want_abs: bool = False):
+    """Forward Y = act(A W + b) with A = (1+eps) X + sum_N X (A is the saved aggregation).
+    Returns dX, dW, db (and their error scales)."""
+    A, W, dY = _f32(A), _f32(W), _f32(dY)
+    dZ = np.where(_f32(Y) > 0, dY, np.float32(0)) if relu else dY
+    db = dZ.astype(np.float64).sum(axis=0).astype(np.float32)
+    dW = _mm64(A.T, dZ).astype(np.float32)
+    dA64 = _mm64(dZ, W.T)
+    dA = dA64.astype(np.float32)
+    rp_t, ci_t = csr_transpose(rowptr, colidx)
+    if not want_abs:
+        return aggregate_gin(rp_t, ci_t, eps, dA), dW, db
+    dX, _ = aggregate_gin(rp_t, ci_t, eps, dA, want_abs=True)
+    dA_abs = _mm64(np.abs(dZ), np.abs(W).T).astype(np.float32)
+    _, s_dX = aggregate_gin(rp_t, ci_t, abs(1.0 + eps) - 1.0, dA_abs, want_abs=True)
+    s_dW = _mm64(np.abs(A).T, np.abs(dZ))
+    s_db = np.abs(dZ).astype(np.float64).sum(axis=0)
+    return (dX, dW, db), (s_dX, s_dW, s_db)

@@ -15,7 +15,7 @@ __all__ = [
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
-    "gnn_version", "alloc_workspace",
+    "gnn_version", "alloc_workspace", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
 ]
 
 GNN_GCN, GNN_GIN = 0, 1
@@ -31,7 +31,7 @@ _SYMBOLS = [
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
-    "gnn_last_hip_error", "gnn_version",
+    "gnn_last_hip_error", "gnn_version", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
 ]
 
 
@@ -62,6 +62,7 @@ def load():
                 "(or __graft_entry__.build()); there is no CPU fallback")
         lib = ctypes.CDLL(_LIB_PATH)
         lib.gnn_workspace_bytes.restype = ctypes.c_size_t
+        lib.gnn_backward_workspace_bytes.restype = ctypes.c_size_t
         lib.gnn_strerror.restype = ctypes.c_char_p
         for name in _SYMBOLS:
             getattr(lib, name)  # AttributeError if the build lost a symbol
@@ -157,6 +158,18 @@ def gnn_apply_perm_csr(rowptr: np.ndarray, colidx: np.ndarray, perm: np.ndarray,
                                    _host(rp2, np.int32, "rowptr2"), _host(ci2, np.int32, "colidx2"),
                                    _host(v2, np.float32, "val2"))
     _check(rc, "gnn_apply_perm_csr")
+    return (rp2, ci2) if val is None else (rp2, ci2, v2)
+
+
+def gnn_csr_transpose(rowptr: np.ndarray, colidx: np.ndarray, val: Optional[np.ndarray] = None):
+    n = rowptr.size - 1
+    rp2 = np.empty(n + 1, dtype=np.int32)
+    ci2 = np.empty(colidx.size, dtype=np.int32)
+    v2 = None if val is None else np.empty(colidx.size, dtype=np.float32)
+    rc = load().gnn_csr_transpose(_i32(n), _host(rowptr, np.int32, "rowptr"), _host(colidx, np.int32, "colidx"),
+                                  _host(val, np.float32, "val"), _host(rp2, np.int32, "rowptr_t"),
+                                  _host(ci2, np.int32, "colidx_t"), _host(v2, np.float32, "val_t"))
+    _check(rc, "gnn_csr_transpose")
     return (rp2, ci2) if val is None else (rp2, ci2, v2)
 
 
@@ -300,6 +313,22 @@ def gnn_layer_forward_timed(kind, n, nnz, rowptr, colidx, ew, eps, X, in_dim, W,
                                         _u32(flags), wp, wb, _stream(stream), _event(ev_agg_start),
                                         _event(ev_agg_stop))
     _check(rc, "gnn_layer_forward_timed")
+
+
+def gnn_backward_workspace_bytes(n: int, nnz: int, in_dim: int, out_dim: int, ngs: int = 0) -> int:
+    return int(load().gnn_backward_workspace_bytes(_i32(n), _i64(nnz), _i32(in_dim), _i32(out_dim), _i32(ngs)))
+
+
+def gnn_layer_backward(kind, n, nnz, rowptr_t, colidx_t, ew_t, eps, P, in_dim, W, out_dim, relu, Y, dY, dX, dW, db,
+                       ngs=0, dw=0, waves_per_block=0, flags=0, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    rc = load().gnn_layer_backward(ctypes.c_int(kind), _i32(n), _i64(nnz), _dev(rowptr_t, "int32", "rowptr_t"),
+                                   _dev(colidx_t, "int32", "colidx_t"), _dev(ew_t, "float32", "ew_t"), _f32(eps),
+                                   _dev(P, "float32", "P"), _i32(in_dim), _dev(W, "float32", "W"), _i32(out_dim),
+                                   ctypes.c_int(1 if relu else 0), _dev(Y, "float32", "Y"), _dev(dY, "float32", "dY"),
+                                   _dev(dX, "float32", "dX"), _dev(dW, "float32", "dW"), _dev(db, "float32", "db"),
+                                   _i32(ngs), _i32(dw), _i32(waves_per_block), _u32(flags), wp, wb, _stream(stream))
+    _check(rc, "gnn_layer_backward")
 
 
 def gnn_permute_rows(n, dim, perm, X, Y, stream=None):

@@ -1,0 +1,321 @@
+// Backward pass of a GNN layer (the paper's training runs reuse the aggregation kernel on
+// gradients, Sec. 7.2 "Training Support"): activation mask, bias gradient, weight gradient
+// (a transposed tall-skinny GEMM reduced over the nodes), input gradient, and the aggregation of
+// gradients over the transposed graph.
+#include <hip/hip_runtime.h>
+
+#include "gnn_internal.h"
+
+namespace gnn {
+
+int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                   const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
+                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes, hipStream_t s,
+                   hipEvent_t ev_start, hipEvent_t ev_stop);
+int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b, int relu,
+                     float *out, hipStream_t s);
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kTnBlocks = 256;  // row chunks of the transposed GEMM (one per CU)
+constexpr int kTnWaves = 4;
+constexpr int kTnPartials = kTnBlocks * kTnWaves;
+
+// dZ = dY where the forward output was positive, else 0 (derivative of ReLU through its output).
+__global__ __launch_bounds__(256) void k_relu_mask(int64_t total, const float *__restrict__ dY,
+                                                   const float *__restrict__ Y, float *__restrict__ dZ)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x)
+        dZ[i] = Y[i] > 0.0f ? dY[i] : 0.0f;
+}
+
+// Column sums of G[n,M], stage 1: block b sums its row chunk into part[b][M].
+__global__ __launch_bounds__(256) void k_colsum_partial(int n, int M, const float *__restrict__ G, float *__restrict__ part)
+{
+    const int64_t rows = ((int64_t)n + gridDim.x - 1) / gridDim.x;
+    const int64_t r0 = (int64_t)blockIdx.x * rows;
+    const int64_t r1 = r0 + rows < n ? r0 + rows : n;
+    for (int c = threadIdx.x; c < M; c += blockDim.x) {
+        float s = 0.0f;
+        for (int64_t r = r0; r < r1; ++r) s += G[(size_t)r * M + c];
+        part[(size_t)blockIdx.x * M + c] = s;
+    }
+}
+
+// Sums groups of `count` consecutive partial arrays of `len` floats:
+// out[g][i] = sum_{p < count} part[g*count + p][i], g = blockIdx.y.
+__global__ __launch_bounds__(256) void k_reduce_partials(int count, int64_t len, const float *__restrict__ part,
+                                                         float *__restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= len) return;
+    const float *src = part + (size_t)blockIdx.y * count * len;
+    float s = 0.0f;
+#pragma unroll 8
+    for (int p = 0; p < count; ++p) s += src[(size_t)p * len + i];
+    out[(size_t)blockIdx.y * len + i] = s;
+}
+
+// Wt[M,K] = W[K,M]^T (small)
+__global__ __launch_bounds__(256) void k_transpose(int K, int M, const float *__restrict__ W, float *__restrict__ Wt)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < K * M) {
+        const int k = i / M, m = i % M;
+        Wt[(size_t)m * K + k] = W[i];
+    }
+}
+
+// C[K,M] = P[n,K]^T Q[n,M], stage 1.  A wave owns KT x MT tiles of 16x16 of the result (offset by
+// blockIdx.y) and walks over its share of the rows four at a time: with v_mfma_f32_16x16x4_f32 the
+// reduction index is the row, so both operands are read straight from global memory, 16 consecutive
+// floats of 4 consecutive rows per instruction.  Every wave writes its partial result; stage 2 sums.
+template <int KT, int MT>
+__global__ __launch_bounds__(256) void k_gemm_tn_partial(int n, int K, int M, const float *__restrict__ P,
+                                                         const float *__restrict__ Q, float *__restrict__ part,
+                                                         int mgroups)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lrow = lane & 15, lk = lane >> 4;
+    const int kg = blockIdx.y / mgroups, mg = blockIdx.y % mgroups;
+    const int k0 = kg * 16 * KT, m0 = mg * 16 * MT;
+    const int64_t rows = (((int64_t)n + gridDim.x - 1) / gridDim.x + 3) / 4 * 4;
+    const int64_t r0 = (int64_t)blockIdx.x * rows;
+    const int64_t r1 = r0 + rows < n ? r0 + rows : n;
+
+    f32x4 acc[KT][MT];
+#pragma unroll
+    for (int a = 0; a < KT; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    for (int64_t r = r0 + 4 * wave; r < r1; r += 4 * kTnWaves) {
+        const int64_t row = r + lk;
+        const bool rv = row < r1;
+        float av[KT], bv[MT];
+#pragma unroll
+        for (int a = 0; a < KT; ++a) {
+            const int k = k0 + a * 16 + lrow;
+            av[a] = (rv && k < K) ? P[(size_t)row * K + k] : 0.0f;
+        }
+#pragma unroll
+        for (int b = 0; b < MT; ++b) {
+            const int m = m0 + b * 16 + lrow;
+            bv[b] = (rv && m < M) ? Q[(size_t)row * M + m] : 0.0f;
+        }
+#pragma unroll
+        for (int a = 0; a < KT; ++a)
+#pragma unroll
+            for (int b = 0; b < MT; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+    }
+
+    // lane holds result rows 4*(lane/16)+i, column lane%16 of each tile
+    float *mine = part + ((size_t)blockIdx.x * kTnWaves + wave) * (size_t)K * M;
+#pragma unroll
+    for (int a = 0; a < KT; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k = k0 + a * 16 + 4 * lk + i, m = m0 + b * 16 + lrow;
+                if (k < K && m < M) mine[(size_t)k * M + m] = acc[a][b][i];
+            }
+}
+
+// Same product with 16-byte loads, for K and M multiples of 4: a lane reads P[row][k0 + 4*lrow .. +3]
+// once and feeds its four values to four different result tiles, so tile a holds the result rows
+// k0 + 4*i + a (i = 0..15) instead of 16 consecutive ones; likewise tile b holds the columns
+// m0 + 4*j + b.  One pair of loads per 16 MFMAs, whole 256-byte row segments per instruction.
+__global__ __launch_bounds__(256) void k_gemm_tn_partial_v4(int n, int K, int M, const float *__restrict__ P,
+                                                            const float *__restrict__ Q, float *__restrict__ part,
+                                                            int mgroups)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lrow = lane & 15, lk = lane >> 4;
+    const int kg = blockIdx.y / mgroups, mg = blockIdx.y % mgroups;
+    const int k0 = kg * 64, m0 = mg * 64;
+    constexpr int kSteps = 4;  // 4-row MFMA steps whose loads are issued together
+    const int64_t rows = (((int64_t)n + gridDim.x - 1) / gridDim.x + 4 * kSteps - 1) / (4 * kSteps) * (4 * kSteps);
+    const int64_t r0 = (int64_t)blockIdx.x * rows;
+    const int64_t r1 = r0 + rows < n ? r0 + rows : n;
+    const bool kin = k0 + 4 * lrow < K, min_ = m0 + 4 * lrow < M;
+
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    for (int64_t r = r0 + 4 * kSteps * wave; r < r1; r += 4 * kSteps * kTnWaves) {
+        float4 pa[kSteps], qb[kSteps];
+#pragma unroll
+        for (int u = 0; u < kSteps; ++u) {
+            const int64_t row = r + 4 * u + lk;
+            const bool rv = row < r1;
+            pa[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            qb[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (rv && kin) pa[u] = *reinterpret_cast<const float4 *>(P + (size_t)row * K + k0 + 4 * lrow);
+            if (rv && min_) qb[u] = *reinterpret_cast<const float4 *>(Q + (size_t)row * M + m0 + 4 * lrow);
+        }
+#pragma unroll
+        for (int u = 0; u < kSteps; ++u) {
+            const float av[4] = {pa[u].x, pa[u].y, pa[u].z, pa[u].w}, bv[4] = {qb[u].x, qb[u].y, qb[u].z, qb[u].w};
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+        }
+    }
+
+    float *mine = part + ((size_t)blockIdx.x * kTnWaves + wave) * (size_t)K * M;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                // MFMA result row 4*lk + i of tile a is k-index k0 + 4*(4*lk + i) + a; column lrow of tile b is m0 + 4*lrow + b
+                const int k = k0 + 4 * (4 * lk + i) + a, m = m0 + 4 * lrow + b;
+                if (k < K && m < M) mine[(size_t)k * M + m] = acc[a][b][i];
+            }
+}
+
+// Sum of the kTnPartials arrays in two levels (32 groups of 32), both with coalesced reads.
+static void reduce_all(int64_t len, float *partials, float *C, hipStream_t s)
+{
+    constexpr int kGroups = 32, kPer = kTnPartials / kGroups;
+    float *mid = partials + (size_t)kTnPartials * len;  // kGroups arrays after the partials
+    const unsigned bx = (unsigned)((len + 255) / 256);
+    hipLaunchKernelGGL(k_reduce_partials, dim3(bx, kGroups), dim3(256), 0, s, kPer, len, partials, mid);
+    hipLaunchKernelGGL(k_reduce_partials, dim3(bx, 1), dim3(256), 0, s, kGroups, len, mid, C);
+}
+
+static int gemm_tn(int32_t n, int32_t K, int32_t M, const float *P, const float *Q, float *C, float *partials,
+                   hipStream_t s)
+{
+    const dim3 block(64 * kTnWaves);
+    const bool v4 = K % 4 == 0 && M % 4 == 0 && ((uintptr_t)P | (uintptr_t)Q) % 16 == 0;
+    if (v4) {
+        const int kgroups = (K + 63) / 64, mgroups = (M + 63) / 64;
+        hipLaunchKernelGGL(k_gemm_tn_partial_v4, dim3(kTnBlocks, (unsigned)(kgroups * mgroups)), block, 0, s, n, K, M, P, Q,
+                           partials, mgroups);
+    } else {
+        // tiles per wave: 4 x up to 4 (16 accumulators of 4 registers)
+        const int ktiles = (K + 15) / 16, mtiles = (M + 15) / 16;
+        const int MT = mtiles >= 4 ? 4 : (mtiles >= 2 ? 2 : 1);
+        const int KT = 4;
+        const int kgroups = (ktiles + KT - 1) / KT, mgroups = (mtiles + MT - 1) / MT;
+        const dim3 grid(kTnBlocks, (unsigned)(kgroups * mgroups));
+        if (MT == 4) hipLaunchKernelGGL((k_gemm_tn_partial<4, 4>), grid, block, 0, s, n, K, M, P, Q, partials, mgroups);
+        else if (MT == 2) hipLaunchKernelGGL((k_gemm_tn_partial<4, 2>), grid, block, 0, s, n, K, M, P, Q, partials, mgroups);
+        else hipLaunchKernelGGL((k_gemm_tn_partial<4, 1>), grid, block, 0, s, n, K, M, P, Q, partials, mgroups);
+    }
+    reduce_all((int64_t)K * M, partials, C, s);
+    GNN_HIP_TRY(hipGetLastError());
+    return GNN_OK;
+}
+
+struct BwdLayout {
+    size_t base;      // partition of the transposed graph (ws_layout without intermediate)
+    size_t dz;        // float[n*out_dim]
+    size_t dh;        // float[n*max(in_dim,out_dim)]
+    size_t wt;        // float[in_dim*out_dim]
+    size_t partials;  // float[(kTnPartials + 32) * in_dim*out_dim] (also holds the bias partials)
+    size_t total;
+};
+
+static BwdLayout bwd_layout(int32_t n, int64_t nnz, int32_t in_dim, int32_t out_dim, int32_t ngs)
+{
+    BwdLayout B;
+    B.base = 0;
+    size_t off = ws_layout(n, nnz, 0, ngs).total;
+    const int32_t mx = in_dim > out_dim ? in_dim : out_dim;
+    B.dz = off;
+    off += align_up(sizeof(float) * (size_t)n * out_dim);
+    B.dh = off;
+    off += align_up(sizeof(float) * (size_t)n * mx);
+    B.wt = off;
+    off += align_up(sizeof(float) * (size_t)in_dim * out_dim);
+    B.partials = off;
+    size_t pb = sizeof(float) * (size_t)(kTnPartials + 32) * in_dim * out_dim;
+    const size_t bb = sizeof(float) * (size_t)kTnBlocks * out_dim;
+    if (pb < bb) pb = bb;
+    off += align_up(pb);
+    B.total = off;
+    return B;
+}
+
+}  // namespace gnn
+
+using namespace gnn;
+
+extern "C" {
+
+size_t gnn_backward_workspace_bytes(int32_t n, int64_t nnz, int32_t in_dim, int32_t out_dim, int32_t ngs)
+{
+    if (n < 0 || nnz < 0 || in_dim <= 0 || out_dim <= 0 || ngs < 0) return 0;
+    // capacity for whatever group size the model may pick when ngs == 0 (ngs = 1 is the upper bound)
+    return bwd_layout(n, nnz, in_dim, out_dim, ngs > 0 ? ngs : 1).total;
+}
+
+int gnn_layer_backward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr_t, const int32_t *colidx_t,
+                       const float *ew_t, float eps, const float *P, int32_t in_dim, const float *W, int32_t out_dim,
+                       int relu, const float *Y, const float *dY, float *dX, float *dW, float *db, int32_t ngs,
+                       int32_t dw, int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
+                       void *stream)
+{
+    if (kind != GNN_GCN && kind != GNN_GIN) return GNN_EINVAL;
+    if (n < 0 || nnz < 0 || nnz >= ((int64_t)1 << 31) || in_dim <= 0 || out_dim <= 0 || ngs < 0) return GNN_EINVAL;
+    if (n == 0) return GNN_OK;
+    if (!P || !W || !dY || !dW || (relu && !Y)) return GNN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int32_t agg_dim = kind == GNN_GCN ? out_dim : in_dim;
+    int32_t ngs_r = ngs, dw_r = dw, wpb_r = waves_per_block;
+    decide_defaults(n, nnz, 0, agg_dim, 1, &ngs_r, &dw_r, &wpb_r);  // only ngs matters here: it fixes the layout
+    const BwdLayout B = bwd_layout(n, nnz, in_dim, out_dim, ngs_r);
+    if (!workspace || ((uintptr_t)workspace) % kAlign != 0 || workspace_bytes < B.total) return GNN_EWORKSPACE;
+    char *ws = (char *)workspace;
+    float *dZbuf = (float *)(ws + B.dz), *dHbuf = (float *)(ws + B.dh), *Wt = (float *)(ws + B.wt);
+    float *partials = (float *)(ws + B.partials);
+    const int64_t total = (int64_t)n * out_dim;
+
+    // through the activation
+    const float *dZ = dY;
+    if (relu) {
+        int64_t blocks = (total + 255) / 256;
+        if (blocks > 8192) blocks = 8192;
+        hipLaunchKernelGGL(k_relu_mask, dim3((unsigned)blocks), dim3(256), 0, s, total, dY, Y, dZbuf);
+        dZ = dZbuf;
+    }
+    if (db) {
+        hipLaunchKernelGGL(k_colsum_partial, dim3(kTnBlocks), dim3(256), 0, s, n, out_dim, dZ, partials);
+        hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)((out_dim + 255) / 256)), dim3(256), 0, s, kTnBlocks,
+                           (int64_t)out_dim, partials, db);
+    }
+    hipLaunchKernelGGL(k_transpose, dim3((unsigned)((in_dim * out_dim + 255) / 256)), dim3(256), 0, s, in_dim, out_dim, W,
+                       Wt);
+    GNN_HIP_TRY(hipGetLastError());
+
+    if (kind == GNN_GCN) {
+        // forward: Y = act(A_hat (X W) + b), P = X.  dH = A_hat^T dZ, dW = X^T dH, dX = dH W^T
+        int rc = aggregate_impl(false, 0.0f, n, nnz, rowptr_t, colidx_t, ew_t, dZ, dHbuf, out_dim, ngs_r, dw,
+                                waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, s, nullptr, nullptr);
+        if (rc != GNN_OK) return rc;
+        rc = gemm_tn(n, in_dim, out_dim, P, dHbuf, dW, partials, s);
+        if (rc != GNN_OK) return rc;
+        if (dX) return update_gemm_impl(n, out_dim, in_dim, dHbuf, Wt, nullptr, 0, dX, s);
+        return GNN_OK;
+    }
+    // GIN forward: Y = act(A W + b) with A = (1+eps) X + sum_N X, P = A.
+    // dW = A^T dZ, dA = dZ W^T, dX = (1+eps) dA + sum over the transposed graph of dA
+    int rc = gemm_tn(n, in_dim, out_dim, P, dZ, dW, partials, s);
+    if (rc != GNN_OK) return rc;
+    if (!dX) return GNN_OK;
+    rc = update_gemm_impl(n, out_dim, in_dim, dZ, Wt, nullptr, 0, dHbuf, s);
+    if (rc != GNN_OK) return rc;
+    return aggregate_impl(true, 1.0f + eps, n, nnz, rowptr_t, colidx_t, nullptr, dHbuf, dX, in_dim, ngs_r, dw,
+                          waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, s, nullptr, nullptr);
+}
+
+}  // extern "C"

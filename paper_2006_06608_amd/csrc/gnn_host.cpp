@@ -161,18 +161,22 @@ void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, in
                      int32_t *wpb)
 {
     (void)max_degree;
-    // dimension workers: lanes per neighbor row.  Each lane moves `vec` floats per load; prefer a
-    // power of two that divides the row exactly (no idle lanes) as long as a lane then owns at
-    // most 4 chunks of the row, else the next power of two above the row length.
+    // dimension workers: lanes per neighbor row.  Each lane moves `vec` floats per load and owns up
+    // to 4 chunks of the row; take the power of two that leaves the fewest lane slots idle
+    // (dw * chunks - row length in vectors), and among equals the widest team (fewest chunks).
     if (*dw <= 0) {
         const int units = (dim + vec - 1) / vec;
-        int d = 1;
-        while (d < 64 && units % (d * 2) == 0) d *= 2;
-        if ((units + d - 1) / d > 4) {
-            d = 1;
-            while (d < 64 && d < units) d *= 2;
+        int best = 64, best_waste = 1 << 30;
+        for (int d = 1; d <= 64; d *= 2) {
+            const int chunks = (units + d - 1) / d;
+            if (chunks > 4) continue;
+            const int waste = d * chunks - units;
+            if (waste <= best_waste) {
+                best_waste = waste;
+                best = d;
+            }
         }
-        *dw = d;
+        *dw = best;
     }
     // neighbor-group size, from the graph alone so that one partition serves every layer of a
     // model.  Time ~ (#groups * per-group cost) + (#entries * per-row cost): bigger groups mean
@@ -272,6 +276,31 @@ int gnn_apply_perm_csr(int32_t n, const int32_t *rowptr, const int32_t *colidx, 
             if (val) val2[rowptr2[r] + k] = val[rowptr[i] + row[k].second];
         }
     }
+    return GNN_OK;
+}
+
+int gnn_csr_transpose(int32_t n, const int32_t *rowptr, const int32_t *colidx, const float *val, int32_t *rowptr_t,
+                      int32_t *colidx_t, float *val_t)
+{
+    if (!rowptr_t || (val && !val_t)) return GNN_EINVAL;
+    const int rc = check_host_csr(n, rowptr, colidx);
+    if (rc != GNN_OK) return rc;
+    const int64_t nnz = rowptr[n];
+    if (nnz > 0 && !colidx_t) return GNN_EINVAL;
+    std::vector<int32_t> fill((size_t)n + 1, 0);
+    for (int64_t e = 0; e < nnz; ++e) fill[colidx[e] + 1]++;
+    rowptr_t[0] = 0;
+    for (int32_t j = 0; j < n; ++j) {
+        rowptr_t[j + 1] = rowptr_t[j] + fill[j + 1];
+        fill[j] = rowptr_t[j];
+    }
+    // rows are visited in ascending order, so every transposed row comes out sorted
+    for (int32_t i = 0; i < n; ++i)
+        for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+            const int32_t pos = fill[colidx[e]]++;
+            colidx_t[pos] = i;
+            if (val) val_t[pos] = val[e];
+        }
     return GNN_OK;
 }
 
