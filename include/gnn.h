@@ -63,6 +63,10 @@ extern "C" {
                                        hold (a block serves <= 64 groups, a wave <= 512 index entries);
                                        without either flag the library pipelines when ngs <= 8, where the
                                        per-tile latency chain dominates */
+#define GNN_FLAG_FUSION 64u         /* gnn_layer_forward(GNN_GIN): fuse the Update GEMM into the aggregation
+                                       kernel where the shape allows (in_dim <= 128 and a multiple of 4,
+                                       out_dim <= 64, <= 4 waves per block).  Opt-in: on the R-MAT
+                                       configuration it is slower than the two separate kernels */
 
 /* ================================================================================== */
 /* HOST-side preparation                                                              */

@@ -24,6 +24,8 @@ namespace gnn {
 int partition_build_impl(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t ngs, void *workspace,
                          size_t workspace_bytes, hipStream_t s);
 size_t pipe_lds_bytes(int T, int dim, int ngs, int dwl_log2, int wpb, bool weighted);
+int try_gin_layer_fused(AggParams &p, int vec, int wpb, const float *W, const float *b, float *out, int M, int relu,
+                        int64_t tiles_upper, bool force, hipStream_t s);
 int pipe_blocks(int vec, int iter, bool weighted, bool self, int cus, int wpb, size_t lds, int64_t tiles_upper, int n);
 int launch_aggregate_pipe(int vec, int iter, bool weighted, bool self, int blocks, int wpb, size_t lds, hipStream_t s,
                           AggParams &p);
@@ -354,6 +356,19 @@ __global__ __launch_bounds__(256) void k_epilogue_all(AggParams p)
         p.out[i] = epilogue(p.out[i], p.bias, (int)(i % p.dim), p.relu);
 }
 
+void launch_agg_init(const AggParams &p, bool self, hipStream_t s)
+{
+    const int64_t blocks = ((int64_t)p.n + 255) / 256;
+    if (self) hipLaunchKernelGGL(k_agg_init<true>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(k_agg_init<false>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+}
+
+void launch_agg_epilogue_spanning(const AggParams &p, hipStream_t s)
+{
+    const int64_t blocks = ((int64_t)p.n + 255) / 256;
+    hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)blocks), dim3(256), 0, s, p);
+}
+
 template <int VEC, int ITER, int U>
 static void launch_main(bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s, const AggParams &p)
 {
@@ -381,7 +396,7 @@ static void launch_vec(int iter, bool weighted, bool self, dim3 grid, dim3 block
 int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
                    const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
                    uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes, hipStream_t s,
-                   hipEvent_t ev_start, hipEvent_t ev_stop)
+                   hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse)
 {
     if (n < 0 || nnz < 0 || nnz >= ((int64_t)1 << 31) || dim <= 0 || ngs < 0 || dw < 0 || wpb < 0) return GNN_EINVAL;
     if (!rowptr || (nnz > 0 && !colidx)) return GNN_EINVAL;
@@ -461,6 +476,20 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     const int64_t init_blocks = ((int64_t)n + 255) / 256;
     const int iter = p.iter_total < 4 ? p.iter_total : 4;
 
+    // GIN layer with the Update fused in (the caller falls back to separate kernels if not taken)
+    if (fuse && (flags & GNN_FLAG_FUSION)) {
+        fuse->done = false;
+        if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
+        const int rc = try_gin_layer_fused(p, vec, wpb, fuse->W, fuse->b, fuse->out, fuse->M, fuse->relu, tiles_upper,
+                                           (flags & GNN_FLAG_FUSION) != 0, s);
+        if (rc < 0) return rc;
+        if (rc == GNN_OK) {
+            if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
+            fuse->done = true;
+            return GNN_OK;
+        }
+    }
+
     // persistent, pipelined kernel whenever its requirements hold
     const bool want_pipe = !(flags & GNN_FLAG_NO_PIPELINE) && ((flags & GNN_FLAG_PIPELINE) || ngs <= 8);
     const size_t plds = want_pipe ? pipe_lds_bytes(T, dim, ngs, dwl_log2, wpb, weighted) : 0;
@@ -523,7 +552,7 @@ int gnn_aggregate_gcn(int32_t n, int64_t nnz, const int32_t *rowptr, const int32
                       uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
 {
     return aggregate_impl(false, 0.0f, n, nnz, rowptr, colidx, ew, X, out, dim, ngs, dw, waves_per_block, flags,
-                          nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream, nullptr, nullptr);
+                          nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream, nullptr, nullptr, nullptr);
 }
 
 int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, float eps,
@@ -531,7 +560,7 @@ int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32
                       uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
 {
     return aggregate_impl(true, 1.0f + eps, n, nnz, rowptr, colidx, nullptr, X, out, dim, ngs, dw, waves_per_block,
-                          flags, nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream, nullptr, nullptr);
+                          flags, nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream, nullptr, nullptr, nullptr);
 }
 
 }  // extern "C"

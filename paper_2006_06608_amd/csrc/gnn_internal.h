@@ -81,6 +81,17 @@ inline WsLayout ws_layout(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs_f
     return L;
 }
 
+// Request to fuse the Update GEMM into a GIN aggregation (gnn_layer_forward); done tells the caller
+// whether the fused kernel was used.
+struct FuseSpec {
+    const float *W;
+    const float *b;
+    float *out;
+    int M;
+    int relu;
+    bool done;
+};
+
 // Host-side record of the last failing HIP status of this thread.
 void set_last_hip_error(int e);
 

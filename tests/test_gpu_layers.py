@@ -50,6 +50,31 @@ def test_layers_with_bias_and_relu(kind, bias):
         LayerChain(gnn.GNN_GIN, g.rowptr, g.colidx, None, 0.3, X, Ws, bs, name="gin").run_to(3)
 
 
+@pytest.mark.parametrize("graph", ["rmat", "batch", "powerlaw"])
+@pytest.mark.parametrize("K,M,ngs,wpb", [(64, 64, 32, 4), (64, 64, 4, 4), (16, 16, 8, 4), (32, 48, 16, 4), (96, 16, 16, 4),
+                                          (128, 64, 8, 4), (40, 24, 8, 2), (64, 3, 16, 4)])
+@pytest.mark.parametrize("bias", [False, True])
+def test_fused_gin_layer_matches_oracle_and_unfused(graph, K, M, ngs, wpb, bias):
+    g = {"rmat": lambda: config_graph(5, shrink=64), "batch": lambda: config_graph(3, shrink=8),
+         "powerlaw": lambda: config_graph(2, shrink=2)}[graph]()
+    rng = np.random.default_rng(K + M)
+    X = features(g.n, K, seed=K)
+    W = glorot(K, M, seed=M)
+    b = rng.standard_normal(M).astype(np.float32) if bias else None
+    ref, scale = oracle.gin_layer(g.rowptr, g.colidx, 0.25, X, W, b, True, want_abs=True)
+    G = DeviceGraph(g.rowptr, g.colidx)
+    ws = gnn.alloc_workspace(G.n, G.nnz, max(K, M), ngs)
+    outs = []
+    for flags in (gnn.GNN_FLAG_FUSION, 0):
+        out = torch.full((g.n, M), float("nan"), device="cuda")
+        gnn.gnn_layer_forward(gnn.GNN_GIN, G.n, G.nnz, G.rowptr, G.colidx, None, 0.25, dev(X), K, dev(W), dev(b), M,
+                              True, out, ngs, 0, wpb, flags, ws)
+        torch.cuda.synchronize()
+        gnn.gnn_workspace_status(ws)
+        outs.append(out.cpu().numpy())
+        assert_parity(outs[-1], ref, scale, f"gin layer {graph} {K}x{M} flags {flags}")
+
+
 def _weights(cfg):
     dims = config_spec(cfg)["dims"]
     return [glorot(dims[i], dims[i + 1], BASE_SEED + cfg, stream=20 + i) for i in range(len(dims) - 1)]
