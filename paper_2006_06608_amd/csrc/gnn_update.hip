@@ -50,16 +50,9 @@ __global__ __launch_bounds__(256) void k_update_gemm(GemmParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col0 = blockIdx.y * MP;
 
-    // W slice -> LDS, zero padded
-    for (int i = tid; i < kpad * MP; i += 256) {
-        const int k = i / MP, c = i % MP;
-        float v = 0.0f;
-        if (k < kslice && col0 + c < p.M) v = p.W[(size_t)(p.k_begin + k) * p.M + col0 + c];
-        s_W[k * LDW + c] = v;
-    }
-
     const int64_t ntiles = ((int64_t)p.n + kGemmRows - 1) / kGemmRows;
     const int lrow = lane & 15, lk = lane >> 4;
+    bool w_staged = false;
 
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t row0 = tile * kGemmRows;
@@ -108,6 +101,26 @@ __global__ __launch_bounds__(256) void k_update_gemm(GemmParams p)
         };
 
         fetch(0);
+        if (!w_staged) {  // after the first A loads are in flight; visible after the barrier below
+            w_staged = true;
+            // W slice -> LDS, zero padded (16-byte loads when the slice is a whole number of float4s)
+            if (p.M % 4 == 0 && ((uintptr_t)p.W & 15) == 0) {
+                constexpr int MQ = MP / 4;
+                for (int i = tid; i < kpad * MQ; i += 256) {
+                    const int k = i / MQ, c = (i % MQ) * 4;
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (k < kslice && col0 + c < p.M) v = *reinterpret_cast<const float4 *>(p.W + (size_t)(p.k_begin + k) * p.M + col0 + c);
+                    *reinterpret_cast<float4 *>(&s_W[k * LDW + c]) = v;
+                }
+            } else {
+                for (int i = tid; i < kpad * MP; i += 256) {
+                    const int k = i / MP, c = i % MP;
+                    float v = 0.0f;
+                    if (k < kslice && col0 + c < p.M) v = p.W[(size_t)(p.k_begin + k) * p.M + col0 + c];
+                    s_W[k * LDW + c] = v;
+                }
+            }
+        }
         for (int kc = 0; kc < kpad; kc += kGemmKC) {
             __syncthreads();  // previous chunk fully consumed (and, first time, W staged)
             commit();
