@@ -146,6 +146,29 @@ def test_block_level_ablation_matches_too():
     assert_parity(run_gin(DeviceGraph(rp, ci), 0.25, X, flags=gnn.GNN_FLAG_NO_BLOCK_OPT), ref, ab, "no block opt gin")
 
 
+def test_unaligned_rows_and_odd_dimensions_take_the_narrow_load_paths():
+    rp, ci = _graph("powerlaw")
+    n = rp.size - 1
+    ew = oracle.gcn_norm(rp, ci)
+    G = DeviceGraph(rp, ci, ew)
+    for dim in (1, 2, 6, 64, 1323):
+        X = features(n, dim, seed=40 + dim)
+        ref, ab = oracle.aggregate_gcn(rp, ci, ew, X, want_abs=True)
+        # tensors that start 4 bytes (and 8 bytes) past a 16-byte boundary
+        for shift in (1, 2):
+            xbuf = torch.zeros(n * dim + 4, device="cuda")
+            obuf = torch.full((n * dim + 4,), float("nan"), device="cuda")
+            Xd = xbuf[shift:shift + n * dim].view(n, dim)
+            Xd.copy_(dev(X))
+            out = obuf[shift:shift + n * dim].view(n, dim)
+            ws = gnn.alloc_workspace(G.n, G.nnz, 0, 0)
+            gnn.gnn_aggregate_gcn(G.n, G.nnz, G.rowptr, G.colidx, G.ew, Xd, out, dim, 0, 0, 0, 0, ws)
+            torch.cuda.synchronize()
+            gnn.gnn_workspace_status(ws)
+            assert_parity(out.cpu().numpy(), ref, ab, f"dim {dim} shift {shift}")
+            assert torch.isnan(obuf[:shift]).all() and torch.isnan(obuf[shift + n * dim:]).all()  # nothing written outside
+
+
 # ------------------------------------------------------------------ degenerate inputs
 def test_empty_graph_single_node_and_isolated_nodes():
     X = features(5, 8, seed=1)
