@@ -63,6 +63,15 @@ extern "C" {
                                        hold (a block serves <= 64 groups, a wave <= 512 index entries);
                                        without either flag the library pipelines when ngs <= 8, where the
                                        per-tile latency chain dominates */
+#define GNN_FLAG_DETERMINISTIC 32u  /* bitwise identical results from run to run (for fixed ngs, dw, waves):
+                                       no float atomics.  The waves of a block add to a shared slot in wave
+                                       order; blocks leave the partial rows of nodes that span blocks in
+                                       scratch memory behind the caller's use of the workspace, and a second
+                                       kernel adds them in block order.  Needs a workspace sized by
+                                       gnn_workspace_bytes with max_dim >= dim (GNN_EWORKSPACE otherwise;
+                                       the size allows for blocks of >= 16 groups, which the automatic
+                                       waves_per_block guarantees); the general kernel is always used; not
+                                       combinable with GNN_FLAG_NO_BLOCK_OPT (GNN_EINVAL) */
 #define GNN_FLAG_FUSION 64u         /* gnn_layer_forward(GNN_GIN): fuse the Update GEMM into the aggregation
                                        kernel where the shape allows (in_dim <= 128 and a multiple of 4,
                                        out_dim <= 64, <= 4 waves per block).  Opt-in: on the R-MAT
@@ -116,7 +125,8 @@ int gnn_paper_model(int32_t dim, int32_t tpw, int32_t tpb, int32_t ngs, int32_t 
 
 /* Bytes of DEVICE workspace (256-byte aligned) that the calls below need for a graph of n
  * nodes / nnz entries, neighbor-group size ngs (0 = whatever the model may pick) and, for
- * gnn_layer_forward, an intermediate of max_dim floats per node (0 for aggregation only). */
+ * gnn_layer_forward, an intermediate of max_dim floats per node (0 for aggregation only).  The size
+ * includes the scratch rows of GNN_FLAG_DETERMINISTIC for rows of up to max_dim floats. */
 size_t gnn_workspace_bytes(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs);
 
 /* Neighbor partitioning (Sec. 4.1): cuts every CSR row into groups of ngs consecutive entries

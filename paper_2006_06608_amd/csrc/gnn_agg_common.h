@@ -17,6 +17,7 @@ struct AggParams {
     const float *ew;
     const float *X;
     float *out;
+    float *det_part;    // deterministic mode: float[2 * tiles * dim] partial rows of spanning nodes; else null
     const float *bias;  // epilogue: out = act(sum + bias); may be null
     float self_scale;   // 1 + eps (GIN)
     int relu;

@@ -30,6 +30,22 @@ int pipe_blocks(int vec, int iter, bool weighted, bool self, int cus, int wpb, s
 int launch_aggregate_pipe(int vec, int iter, bool weighted, bool self, int blocks, int wpb, size_t lds, hipStream_t s,
                           AggParams &p);
 
+// The workspace does not hold the partition the launch was prepared for: record why nothing was
+// computed (one thread).
+__device__ inline void note_stale(WsHeader *hdr, const AggParams &p)
+{
+    if (hdr->magic != kMagic) {
+        hdr->magic = kMagic;
+        hdr->n = p.n;
+        hdr->nnz = p.nnz;
+        hdr->ngs = 0;
+        hdr->num_ng = 0;
+        hdr->status = GNN_ESTALE;
+    } else if (hdr->status == GNN_OK) {
+        hdr->status = GNN_ESTALE;
+    }
+}
+
 // Rows the main kernel will not store plainly: rows without entries get their final value, rows
 // whose groups span several blocks are zeroed for the atomic adds.  One wave scans 64 nodes.
 template <bool SELF>
@@ -37,19 +53,7 @@ __global__ __launch_bounds__(256) void k_agg_init(AggParams p)
 {
     WsHeader *hdr = p.hdr;
     if (!header_ok(hdr, p)) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            // record why nothing was computed
-            if (hdr->magic != kMagic) {
-                hdr->magic = kMagic;
-                hdr->n = p.n;
-                hdr->nnz = p.nnz;
-                hdr->ngs = 0;
-                hdr->num_ng = 0;
-                hdr->status = GNN_ESTALE;
-            } else if (hdr->status == GNN_OK) {
-                hdr->status = GNN_ESTALE;
-            }
-        }
+        if (blockIdx.x == 0 && threadIdx.x == 0) note_stale(hdr, p);
         return;
     }
     const int lane = threadIdx.x & 63;
@@ -270,7 +274,7 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
                         else store_vec<VEC>(p.out + (size_t)e.node * dim + d, r);
                     }
                 }
-            } else {
+            } else if (!p.det_part) {
                 // the node continues in another wave (or block): accumulate in its LDS slot
                 float *srow = s_slot + (size_t)slot * dim;
 #pragma unroll
@@ -282,6 +286,27 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
                     }
                 }
                 if (lastflag != 0 && tlane == 0) s_last[slot] = 1;
+            }
+        }
+        if (p.det_part) {
+            // deterministic mode: the waves add to the slots one after the other, in wave order (the
+            // segment heads of one wave have distinct target nodes, so plain read-modify-writes do)
+            const bool add = seg_head && !complete_in_wave;
+            const int nw = blockDim.x >> 6;
+            for (int w = 0; w < nw; ++w) {
+                if ((tid >> 6) == w && add) {
+                    float *srow = s_slot + (size_t)slot * dim;
+#pragma unroll
+                    for (int c = 0; c < ITER; ++c) {
+                        const int d = ((c0 + c) * dwl + tlane) * VEC;
+                        if (d < dim) {
+#pragma unroll
+                            for (int j = 0; j < VEC; ++j) srow[d + j] += acc[c][j];
+                        }
+                    }
+                    if (lastflag != 0 && tlane == 0) s_last[slot] = 1;
+                }
+                __syncthreads();
             }
         }
     }
@@ -309,10 +334,79 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
                 for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
                 if (p.stream_out) store_vec_stream<VEC>(orow + d, r);
                 else store_vec<VEC>(orow + d, r);
+            } else if (p.det_part) {
+                // the node of the block's first group goes to partial row 0 of the tile, any other
+                // unfinished node (it can only be the node of the last group) to partial row 1
+                store_vec<VEC>(p.det_part + ((size_t)tile * 2 + (lay.team == 0 ? 0 : 1)) * dim + d, r);
             } else {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) atomicAdd(&orow[d + j], r[j]);
             }
+        }
+    }
+}
+
+// Deterministic mode, second pass: a node whose groups span the tiles b0..b1 is the sum of those
+// tiles' partial rows, added in tile order, then bias/activation.  One wave scans 64 nodes, lists
+// the spanning ones and lets its teams finish them side by side.
+template <int VEC>
+__global__ __launch_bounds__(256) void k_agg_det_finish(AggParams p)
+{
+    __shared__ int s_list[256];
+    if (!header_ok(p.hdr, p)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) note_stale(p.hdr, p);
+        return;
+    }
+    const int lane = threadIdx.x & 63;
+    const int dwl = 1 << p.dwl_log2, G = 64 >> p.dwl_log2;
+    const int tlane = lane & (dwl - 1), team_in_wave = lane >> p.dwl_log2;
+    int *mylist = s_list + (threadIdx.x & ~63);
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t v = wave * 64 + lane;
+    int c0 = 0, c1 = 0;
+    if (v < p.n) {
+        c0 = p.ngptr[v];
+        c1 = p.ngptr[v + 1];
+    }
+    const bool spans = c1 > c0 && c0 / p.T != (c1 - 1) / p.T;
+    const unsigned long long m = __ballot(spans);
+    if (m == 0ull) return;
+    const int cnt = __popcll(m);
+    if (spans) mylist[__popcll(m & ((1ull << lane) - 1ull))] = lane;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int dim = p.dim;
+    for (int k0 = 0; k0 < cnt; k0 += G) {
+        const int k = k0 + team_in_wave;
+        const int l = k < cnt ? mylist[k] : 0;
+        const int g0 = __shfl(c0, l), g1 = __shfl(c1, l);
+        if (k >= cnt) continue;
+        const int64_t b0 = g0 / p.T, b1 = (g1 - 1) / p.T;
+        float *row = p.out + (size_t)(wave * 64 + l) * dim;
+        for (int c = 0; c < p.iter_total; ++c) {
+            const int d = (c * dwl + tlane) * VEC;
+            if (d >= dim) break;
+            // in its first tile the node is the tile's first node only if it starts the tile
+            float sum[VEC];
+            load_vec<VEC>(sum, p.det_part + ((size_t)b0 * 2 + (g0 % p.T == 0 ? 0 : 1)) * dim + d);
+            for (int64_t b = b0 + 1; b <= b1; b += 4) {
+                float t[4][VEC];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) t[q][j] = 0.0f;
+                    if (b + q <= b1) load_vec<VEC>(t[q], p.det_part + ((size_t)(b + q) * 2) * dim + d);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (b + q <= b1) {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) sum[j] += t[q][j];
+                    }
+            }
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) sum[j] = epilogue(sum[j], p.bias, d + j, p.relu);
+            store_vec<VEC>(row + d, sum);
         }
     }
 }
@@ -392,11 +486,13 @@ static void launch_vec(int iter, bool weighted, bool self, dim3 grid, dim3 block
 }
 
 // Shared implementation of gnn_aggregate_gcn / gnn_aggregate_gin and of the aggregation step of
-// gnn_layer_forward.  self: add self_scale * X[i] (GIN).  bias/relu: fused epilogue.
+// gnn_layer_forward.  self: add self_scale * X[i] (GIN).  bias/relu: fused epilogue.  ws_reserved:
+// bytes at the front of the workspace that the caller uses itself (0: only the partition); the
+// scratch of the deterministic mode is placed behind them.
 int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
                    const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
-                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes, hipStream_t s,
-                   hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse)
+                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes,
+                   size_t ws_reserved, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse)
 {
     if (n < 0 || nnz < 0 || nnz >= ((int64_t)1 << 31) || dim <= 0 || ngs < 0 || dw < 0 || wpb < 0) return GNN_EINVAL;
     if (!rowptr || (nnz > 0 && !colidx)) return GNN_EINVAL;
@@ -404,7 +500,10 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     if (X == out && n > 0) return GNN_EINVAL;
     if (dw > 64 || (dw & (dw - 1)) != 0) return GNN_EINVAL;
     if (wpb > kMaxWavesPerBlock) return GNN_EINVAL;
+    const bool det = (flags & GNN_FLAG_DETERMINISTIC) != 0;
+    if (det && (flags & GNN_FLAG_NO_BLOCK_OPT)) return GNN_EINVAL;
     if (n == 0) return GNN_OK;
+    const bool auto_wpb = wpb == 0;
 
     const int vec = pick_vec(dim, X, out);
 
@@ -429,6 +528,7 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     p.ew = ew;
     p.X = X;
     p.out = out;
+    p.det_part = nullptr;
     p.bias = bias;
     p.self_scale = self_scale;
     p.relu = relu;
@@ -464,6 +564,9 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
         return GNN_OK;
     }
 
+    // the workspace-size functions allow deterministic scratch for blocks of kDetMinTile groups
+    if (det && auto_wpb)
+        while (wpb * (64 >> dwl_log2) < kDetMinTile && wpb < kMaxWavesPerBlock) wpb *= 2;
     const int T = wpb * (64 >> dwl_log2);
     p.T = T;
     size_t lds = (size_t)(kMaxWavesPerBlock + T + (size_t)T * ngs * (weighted ? 2 : 1)) * 4;
@@ -476,8 +579,15 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     const int64_t init_blocks = ((int64_t)n + 255) / 256;
     const int iter = p.iter_total < 4 ? p.iter_total : 4;
 
+    if (det) {
+        size_t off = L.total > ws_reserved ? L.total : ws_reserved;
+        off = align_up(off);
+        if (off + det_scratch_bytes(ng_cap, T, dim) > workspace_bytes) return GNN_EWORKSPACE;
+        p.det_part = (float *)(ws + off);
+    }
+
     // GIN layer with the Update fused in (the caller falls back to separate kernels if not taken)
-    if (fuse && (flags & GNN_FLAG_FUSION)) {
+    if (fuse && (flags & GNN_FLAG_FUSION) && !det) {
         fuse->done = false;
         if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
         const int rc = try_gin_layer_fused(p, vec, wpb, fuse->W, fuse->b, fuse->out, fuse->M, fuse->relu, tiles_upper,
@@ -491,7 +601,7 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     }
 
     // persistent, pipelined kernel whenever its requirements hold
-    const bool want_pipe = !(flags & GNN_FLAG_NO_PIPELINE) && ((flags & GNN_FLAG_PIPELINE) || ngs <= 8);
+    const bool want_pipe = !det && !(flags & GNN_FLAG_NO_PIPELINE) && ((flags & GNN_FLAG_PIPELINE) || ngs <= 8);
     const size_t plds = want_pipe ? pipe_lds_bytes(T, dim, ngs, dwl_log2, wpb, weighted) : 0;
     if (plds > 0 && plds <= kMaxLdsBytes) {
         int dev = 0, cus = 0;
@@ -525,7 +635,9 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     p.extra_blocks = (int)extra;
     if (grid + extra >= ((int64_t)1 << 31)) return GNN_ELIMIT;
 
-    if (self) hipLaunchKernelGGL(k_agg_init<true>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+    // (the deterministic mode adds nothing to `out`, so no row needs zeroing)
+    if (det) {
+    } else if (self) hipLaunchKernelGGL(k_agg_init<true>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
     else hipLaunchKernelGGL(k_agg_init<false>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
 
     if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
@@ -536,7 +648,11 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
         else launch_vec<1>(iter, weighted, self, g, b, lds, s, p);
     }
     if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
-    if (bias || relu) hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+    if (det) {
+        if (vec == 4) hipLaunchKernelGGL(k_agg_det_finish<4>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+        else if (vec == 2) hipLaunchKernelGGL(k_agg_det_finish<2>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL(k_agg_det_finish<1>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+    } else if (bias || relu) hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
     GNN_HIP_TRY(hipGetLastError());
     return GNN_OK;
 }
@@ -552,7 +668,7 @@ int gnn_aggregate_gcn(int32_t n, int64_t nnz, const int32_t *rowptr, const int32
                       uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
 {
     return aggregate_impl(false, 0.0f, n, nnz, rowptr, colidx, ew, X, out, dim, ngs, dw, waves_per_block, flags,
-                          nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream, nullptr, nullptr, nullptr);
+                          nullptr, 0, workspace, workspace_bytes, 0, (hipStream_t)stream, nullptr, nullptr, nullptr);
 }
 
 int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, float eps,
@@ -560,7 +676,8 @@ int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32
                       uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
 {
     return aggregate_impl(true, 1.0f + eps, n, nnz, rowptr, colidx, nullptr, X, out, dim, ngs, dw, waves_per_block,
-                          flags, nullptr, 0, workspace, workspace_bytes, (hipStream_t)stream, nullptr, nullptr, nullptr);
+                          flags, nullptr, 0, workspace, workspace_bytes, 0, (hipStream_t)stream, nullptr, nullptr,
+                          nullptr);
 }
 
 }  // extern "C"

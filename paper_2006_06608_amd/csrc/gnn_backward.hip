@@ -10,8 +10,8 @@ namespace gnn {
 
 int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
                    const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
-                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes, hipStream_t s,
-                   hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse);
+                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes,
+                   size_t ws_reserved, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse);
 int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b, int relu,
                      float *out, hipStream_t s);
 
@@ -256,7 +256,9 @@ size_t gnn_backward_workspace_bytes(int32_t n, int64_t nnz, int32_t in_dim, int3
 {
     if (n < 0 || nnz < 0 || in_dim <= 0 || out_dim <= 0 || ngs < 0) return 0;
     // capacity for whatever group size the model may pick when ngs == 0 (ngs = 1 is the upper bound)
-    return bwd_layout(n, nnz, in_dim, out_dim, ngs > 0 ? ngs : 1).total;
+    const int32_t cap_ngs = ngs > 0 ? ngs : 1;
+    return bwd_layout(n, nnz, in_dim, out_dim, cap_ngs).total +
+           det_scratch_bytes(ng_upper_bound(n, nnz, cap_ngs), kDetMinTile, in_dim > out_dim ? in_dim : out_dim);
 }
 
 int gnn_layer_backward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr_t, const int32_t *colidx_t,
@@ -300,7 +302,8 @@ int gnn_layer_backward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr_t
     if (kind == GNN_GCN) {
         // forward: Y = act(A_hat (X W) + b), P = X.  dH = A_hat^T dZ, dW = X^T dH, dX = dH W^T
         int rc = aggregate_impl(false, 0.0f, n, nnz, rowptr_t, colidx_t, ew_t, dZ, dHbuf, out_dim, ngs_r, dw,
-                                waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, s, nullptr, nullptr, nullptr);
+                                waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, B.total, s, nullptr, nullptr,
+                                nullptr);
         if (rc != GNN_OK) return rc;
         rc = gemm_tn(n, in_dim, out_dim, P, dHbuf, dW, partials, s);
         if (rc != GNN_OK) return rc;
@@ -315,7 +318,8 @@ int gnn_layer_backward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr_t
     rc = update_gemm_impl(n, out_dim, in_dim, dZ, Wt, nullptr, 0, dHbuf, s);
     if (rc != GNN_OK) return rc;
     return aggregate_impl(true, 1.0f + eps, n, nnz, rowptr_t, colidx_t, nullptr, dHbuf, dX, in_dim, ngs_r, dw,
-                          waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, s, nullptr, nullptr, nullptr);
+                          waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, B.total, s, nullptr, nullptr,
+                          nullptr);
 }
 
 }  // extern "C"

@@ -81,6 +81,18 @@ inline WsLayout ws_layout(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs_f
     return L;
 }
 
+// Deterministic mode (GNN_FLAG_DETERMINISTIC): every block may leave up to two partial rows (the
+// node of its first and of its last neighbor group) in scratch memory behind the caller's own use
+// of the workspace.  The workspace-size functions allow for blocks of at least kDetMinTile groups.
+constexpr int kDetMinTile = 16;
+
+inline size_t det_scratch_bytes(int64_t ng_capacity, int tile, int32_t dim)
+{
+    if (dim <= 0) return 0;
+    const int64_t tiles = (ng_capacity + tile - 1) / tile;
+    return align_up(sizeof(float) * 2 * (size_t)(tiles > 0 ? tiles : 1) * (size_t)dim);
+}
+
 // Request to fuse the Update GEMM into a GIN aggregation (gnn_layer_forward); done tells the caller
 // whether the fused kernel was used.
 struct FuseSpec {

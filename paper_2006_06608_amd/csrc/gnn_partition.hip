@@ -249,7 +249,8 @@ extern "C" {
 size_t gnn_workspace_bytes(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs)
 {
     if (n < 0 || nnz < 0 || max_dim < 0 || ngs < 0) return 0;
-    return ws_layout(n, nnz, max_dim, ngs).total;
+    const WsLayout L = ws_layout(n, nnz, max_dim, ngs);
+    return L.total + det_scratch_bytes(L.ng_capacity, kDetMinTile, max_dim);
 }
 
 int gnn_partition_build(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t ngs, void *workspace,

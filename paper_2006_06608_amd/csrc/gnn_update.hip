@@ -14,8 +14,8 @@ namespace gnn {
 
 int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
                    const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
-                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes, hipStream_t s,
-                   hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse);
+                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes,
+                   size_t ws_reserved, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse);
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -367,12 +367,12 @@ int gnn_layer_forward_timed(int kind, int32_t n, int64_t nnz, const int32_t *row
         int rc = update_gemm_impl(n, in_dim, out_dim, X, W, nullptr, 0, tmp, s);
         if (rc != GNN_OK) return rc;
         return aggregate_impl(false, 0.0f, n, nnz, rowptr, colidx, ew, tmp, out, out_dim, ngs_r, dw, waves_per_block,
-                              flags, b, relu, workspace, workspace_bytes, s, ev0, ev1, nullptr);
+                              flags, b, relu, workspace, workspace_bytes, L.total, s, ev0, ev1, nullptr);
     }
     FuseSpec fuse = {W, b, out, out_dim, relu, false};
     int rc = aggregate_impl(true, 1.0f + eps, n, nnz, rowptr, colidx, nullptr, X, tmp, in_dim, ngs_r, dw,
-                            waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, s, ev0, ev1,
-                            &fuse);
+                            waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, L.total, s, ev0,
+                            ev1, &fuse);
     if (rc != GNN_OK) return rc;
     if (fuse.done) return GNN_OK;
     return update_gemm_impl(n, in_dim, out_dim, tmp, W, b, relu, out, s);

@@ -1,0 +1,118 @@
+"""GNN_FLAG_DETERMINISTIC: no float atomics, so repeated runs agree bit for bit; values still match the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2006_06608_amd as gnn
+from gnn_synth import config_graph, features, glorot
+from util import csr_from_edges
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import DeviceGraph, assert_parity, dev, run_gcn, run_gin
+
+DET = gnn.GNN_FLAG_DETERMINISTIC
+
+
+def _graph(kind):
+    if kind == "powerlaw":
+        g = config_graph(2, shrink=4)
+        return g.rowptr, g.colidx
+    if kind == "rmat":
+        g = config_graph(5, shrink=64)
+        return g.rowptr, g.colidx
+    if kind == "star":  # one row that spans every block, the rest are single entries
+        n = 6001
+        return csr_from_edges(n, [(0, i) for i in range(1, n)], self_loops=True)
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("kind", ["powerlaw", "rmat", "star"])
+@pytest.mark.parametrize("dim,ngs,dw,wpb", [(64, 0, 0, 0), (16, 4, 4, 4), (64, 2, 16, 8), (22, 8, 0, 0), (3, 1, 1, 1),
+                                            (96, 16, 8, 3), (130, 8, 64, 0), (64, 32, 64, 16)])
+def test_repeated_runs_are_bitwise_identical_and_match_the_oracle(kind, dim, ngs, dw, wpb):
+    rp, ci = _graph(kind)
+    n = rp.size - 1
+    X = features(n, dim, seed=900 + dim)
+    ew = oracle.gcn_norm(rp, ci)
+    G = DeviceGraph(rp, ci, ew)
+    ws = gnn.alloc_workspace(G.n, G.nnz, dim, ngs)
+    ref, ab = oracle.aggregate_gcn(rp, ci, ew, X, want_abs=True)
+    first = run_gcn(G, X, ngs=ngs, dw=dw, wpb=wpb, flags=DET, ws=ws)
+    assert_parity(first, ref, ab, f"deterministic gcn {kind} dim {dim}")
+    run_gcn(G, X, ngs=ngs, dw=dw, wpb=wpb, ws=ws)  # a default (atomic) run in between leaves no trace
+    for _ in range(3):
+        again = run_gcn(G, X, ngs=ngs, dw=dw, wpb=wpb, flags=DET | gnn.GNN_FLAG_REUSE_PARTITION, ws=ws)
+        assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
+    G2 = DeviceGraph(rp, ci)
+    ref, ab = oracle.aggregate_gin(rp, ci, 0.25, X, want_abs=True)
+    first = run_gin(G2, 0.25, X, ngs=ngs, dw=dw, wpb=wpb, flags=DET, ws=ws)
+    assert_parity(first, ref, ab, f"deterministic gin {kind} dim {dim}")
+    for _ in range(3):
+        again = run_gin(G2, 0.25, X, ngs=ngs, dw=dw, wpb=wpb, flags=DET, ws=ws)
+        assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
+
+
+@pytest.mark.parametrize("kind_id", ["gcn", "gin"])
+def test_deterministic_layers_with_bias_and_relu(kind_id):
+    rp, ci = _graph("rmat")
+    n = rp.size - 1
+    K, M = 64, 48
+    X = features(n, K, seed=77)
+    W = glorot(K, M, seed=78)
+    b = features(1, M, seed=79)[0] * 0.1
+    ngs = 4  # small groups: many rows span blocks, so the second pass applies the epilogue to many rows
+    if kind_id == "gcn":
+        ew = oracle.gcn_norm(rp, ci)
+        G = DeviceGraph(rp, ci, ew)
+        ref, scale = oracle.gcn_layer(rp, ci, ew, X, W, b, True, want_abs=True)
+        kind = gnn.GNN_GCN
+    else:
+        G = DeviceGraph(rp, ci)
+        ref, scale = oracle.gin_layer(rp, ci, 0.0, X, W, b, True, want_abs=True)
+        kind = gnn.GNN_GIN
+    ws = gnn.alloc_workspace(G.n, G.nnz, max(K, M), ngs)
+    Xd, Wd, bd = dev(X), dev(W), dev(b)
+    outs = []
+    for _ in range(3):
+        out = torch.full((n, M), float("nan"), device="cuda")
+        gnn.gnn_layer_forward(kind, G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, Xd, K, Wd, bd, M, True, out, ngs, 0, 0,
+                              DET, ws)
+        torch.cuda.synchronize()
+        gnn.gnn_workspace_status(ws)
+        outs.append(out.cpu().numpy())
+    assert_parity(outs[0], ref, scale, f"deterministic {kind_id} layer")
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+    assert np.array_equal(outs[0].view(np.uint32), outs[2].view(np.uint32))
+
+
+def test_deterministic_mode_argument_errors():
+    rp, ci = _graph("powerlaw")
+    G = DeviceGraph(rp, ci)
+    X = dev(features(G.n, 16, seed=1))
+    out = torch.empty_like(X)
+    small = gnn.alloc_workspace(G.n, G.nnz, 0, 8)  # sized without rows for the partial sums
+    with pytest.raises(gnn.GnnError) as e:
+        gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, X, out, 16, 8, 0, 0, DET, small)
+    assert e.value.code == -3  # GNN_EWORKSPACE
+    ws = gnn.alloc_workspace(G.n, G.nnz, 16, 8)
+    with pytest.raises(gnn.GnnError) as e:
+        gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, X, out, 16, 8, 0, 0, DET | gnn.GNN_FLAG_NO_BLOCK_OPT, ws)
+    assert e.value.code == -1  # GNN_EINVAL
+
+
+def test_deterministic_full_size_rmat():
+    """Configuration 5 at full size (hubs of up to 39,649 entries span dozens of blocks)."""
+    g = config_graph(5)
+    n, dim = g.n, 64
+    X = features(n, dim, seed=5)
+    G = DeviceGraph(g.rowptr, g.colidx)
+    ws = gnn.alloc_workspace(G.n, G.nnz, dim, 0)
+    first = run_gin(G, 0.0, X, flags=DET, ws=ws)
+    for _ in range(2):
+        again = run_gin(G, 0.0, X, flags=DET | gnn.GNN_FLAG_REUSE_PARTITION, ws=ws)
+        assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
+    ref, ab = oracle.aggregate_gin(g.rowptr, g.colidx, 0.0, X, want_abs=True)
+    assert_parity(first, ref, ab, "deterministic config 5")
