@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--flags", type=int, default=0, help="extra GNN_FLAG_* bits for the aggregation")
     ap.add_argument("--renumber", action="store_true", help="apply gnn_reorder (forced) before the run")
     ap.add_argument("--hidden", type=int, default=0, help="override the hidden dimension of the model (sweep)")
+    ap.add_argument("--replicate", type=int, default=1,
+                    help="run on this many disjoint copies of the configuration's graph (e.g. --config 3 "
+                         "--replicate 43: a Type II batch of 1.9 M nodes)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step in a HIP graph and time replays (launch-bound small configurations)")
     ap.add_argument("--train", action="store_true",
@@ -70,7 +73,7 @@ def main():
     import torch
 
     import paper_2006_06608_amd as gnn
-    from gnn_synth import BASE_SEED, config_graph, config_spec, features, glorot
+    from gnn_synth import BASE_SEED, config_graph, config_spec, features, glorot, replicate
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -78,7 +81,7 @@ def main():
     spec = config_spec(cfg)
     kind = "gin" if spec["kind"] == "gin" else "gcn"
     t0 = time.time()
-    g = config_graph(cfg)
+    g = replicate(config_graph(cfg), args.replicate)
     rp_h, ci_h = g.rowptr, g.colidx
     n, nnz = g.n, g.nnz
     dims = list(spec["dims"])
@@ -325,12 +328,14 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"cfg{cfg}: {spec['desc']}; n={n}, directed entries={nnz}, layers={layers}",
+        "config": {"workload": f"cfg{cfg}{'' if args.replicate == 1 else f' x{args.replicate} copies'}: {spec['desc']}; "
+                               f"n={n}, directed entries={nnz}, layers={layers}",
                    "ngs": ngs, "dw": args.dw or dw, "waves_per_block": args.wpb or wpb, "neighbor_groups": num_ng,
                    "renumbered": bool(args.renumber), "flags": args.flags},
         "roofline": {"bound": "hbm", "kernel": f"{kname} ({kind.upper()}, Dim {dom_dim})", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, ngs, bool(args.renumber))),
+                     "traffic": (MEASURED_TRAFFIC_BYTES.get((cfg, ngs, bool(args.renumber)))
+                                 if args.replicate == 1 and not args.hidden and not args.flags else None),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_kernel_ms": dom_ms},
         "cpu_baseline": cpu,
         "aggregation_kernel_ms_per_layer": [float(x) for x in agg_ms_layers],

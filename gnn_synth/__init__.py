@@ -17,6 +17,7 @@ from .graphs import (  # noqa: F401
     glorot,
     planted_community_graph,
     power_law_graph,
+    replicate,
     rmat_graph,
     shuffle_ids,
 )

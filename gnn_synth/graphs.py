@@ -258,6 +258,20 @@ def block_diagonal_batch(num_graphs: int, mean_nodes: float, edge_factor: float,
     return Graph(n, rp, ci, name, {"num_graphs": num_graphs, "graph_sizes": sizes})
 
 
+def replicate(g: Graph, copies: int) -> Graph:
+    """Block-diagonal union of `copies` disjoint copies of g, ids offset per copy (a larger batch of
+    the same family: the shape of the paper's big Type II sets, millions of nodes in small graphs)."""
+    if copies <= 1:
+        return g
+    n, nnz = g.n, g.nnz
+    assert copies * n < 2 ** 31 and copies * nnz < 2 ** 31
+    off_n = (np.arange(copies, dtype=np.int64) * n)[:, None]
+    off_e = (np.arange(copies, dtype=np.int64) * nnz)[:, None]
+    rp = np.concatenate([(g.rowptr[None, :-1].astype(np.int64) + off_e).ravel(), [copies * nnz]]).astype(np.int32)
+    ci = (g.colidx[None, :].astype(np.int64) + off_n).ravel().astype(np.int32)
+    return Graph(copies * n, rp, ci, f"{g.name}x{copies}", {"copies": copies})
+
+
 def rmat_graph(scale: int, n_pairs: int, a: float, b: float, c: float, seed: int,
                scramble: bool = True, name: str = "rmat") -> Graph:
     """R-MAT: n_pairs sampled undirected pairs on 2^scale nodes, symmetrised, de-duplicated, loops dropped."""
