@@ -174,7 +174,7 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
     const int slot = block_layout_slot(lay, dwl_log2, s_wave_cnt);
 
     const int len = lay.valid ? e.end - e.start : 0;
-    const int off = e.start - e0;
+    const int off = lay.valid ? e.start - e0 : 0;
     const bool first = (e.flags & 1) != 0;
 
     // teams that continue the node of the team before them in the same wave
@@ -187,23 +187,36 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
     for (int c0 = 0; c0 < p.iter_total; c0 += ITER) {
         float acc[ITER][VEC];
         bool dok[ITER];
+        const float *xb = p.X + (size_t)(c0 * dwl + tlane) * VEC;
 #pragma unroll
         for (int c = 0; c < ITER; ++c) {
             dok[c] = ((c0 + c) * dwl + tlane) * VEC < dim;
 #pragma unroll
             for (int j = 0; j < VEC; ++j) acc[c][j] = 0.0f;
+            // GIN: the node's own row enters the sum with the first group of the node, as one more
+            // term, so its load overlaps with the neighbour loads instead of following them
+            if (SELF && first && len > 0 && dok[c]) {
+                float xs[VEC];
+                load_vec<VEC>(xs, xb + (size_t)e.node * dim + (size_t)c * dwl * VEC);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[c][j] = p.self_scale * xs[j];
+            }
         }
-        const float *xb = p.X + (size_t)(c0 * dwl + tlane) * VEC;
 
         for (int base = 0; base < len; base += U) {
             int col[U];
             float w[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                // read first, select after: positions past the group still lie inside the block's LDS
                 const int k = base + u;
                 const bool a = k < len;
-                col[u] = a ? s_col[off + k] : -1;
-                if (WEIGHTED) w[u] = a ? s_w[off + k] : 0.0f;
+                const int cu = s_col[off + k];
+                col[u] = a ? cu : -1;
+                if (WEIGHTED) {
+                    const float wu = s_w[off + k];
+                    w[u] = a ? wu : 0.0f;
+                }
             }
             float v[U][ITER][VEC];
 #pragma unroll
@@ -211,7 +224,8 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 #pragma unroll
                 for (int c = 0; c < ITER; ++c) {
                     if (col[u] >= 0 && dok[c]) {
-                        load_vec<VEC>(v[u][c], xb + (size_t)col[u] * dim + (size_t)c * dwl * VEC);
+                        // 32 x 32 -> 64-bit product: one multiply-add per address
+                        load_vec<VEC>(v[u][c], xb + (size_t)(unsigned)col[u] * (unsigned)dim + (size_t)c * dwl * VEC);
                     } else {
 #pragma unroll
                         for (int j = 0; j < VEC; ++j) v[u][c][j] = 0.0f;
@@ -259,17 +273,8 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
                     const int d = ((c0 + c) * dwl + tlane) * VEC;
                     if (d < dim) {
                         float r[VEC];
-                        if (SELF) {
-                            float xs[VEC];
-                            load_vec<VEC>(xs, p.X + (size_t)e.node * dim + d);
 #pragma unroll
-                            for (int j = 0; j < VEC; ++j) r[j] = fmaf(p.self_scale, xs[j], acc[c][j]);
-                        } else {
-#pragma unroll
-                            for (int j = 0; j < VEC; ++j) r[j] = acc[c][j];
-                        }
-#pragma unroll
-                        for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
+                        for (int j = 0; j < VEC; ++j) r[j] = epilogue(acc[c][j], p.bias, d + j, p.relu);
                         if (p.stream_out) store_vec_stream<VEC>(p.out + (size_t)e.node * dim + d, r);
                         else store_vec<VEC>(p.out + (size_t)e.node * dim + d, r);
                     }
@@ -323,12 +328,6 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
             float r[VEC];
 #pragma unroll
             for (int j = 0; j < VEC; ++j) r[j] = srow[d + j];
-            if (SELF && first) {
-                float xs[VEC];
-                load_vec<VEC>(xs, p.X + (size_t)e.node * dim + d);
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) r[j] = fmaf(p.self_scale, xs[j], r[j]);
-            }
             if (complete) {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
