@@ -39,7 +39,7 @@ def _graph(name):
     raise ValueError(name)
 
 
-def _run_backward(kind, rp, ci, ew, eps, P, W, relu, Y, dY, want_dx=True, want_db=True):
+def _run_backward(kind, rp, ci, ew, eps, P, W, relu, Y, dY, want_dx=True, want_db=True, flags=0):
     n, K = P.shape
     M = W.shape[1]
     if ew is None:
@@ -54,7 +54,7 @@ def _run_backward(kind, rp, ci, ew, eps, P, W, relu, Y, dY, want_dx=True, want_d
     dW = torch.full((K, M), float("nan"), device="cuda")
     db = torch.full((M,), float("nan"), device="cuda") if want_db else None
     gnn.gnn_layer_backward(kind, n, G.nnz, G.rowptr, G.colidx, G.ew, eps, dev(P), K, dev(W), M, relu, dev(Y), dev(dY),
-                           dX, dW, db, 0, 0, 0, 0, ws)
+                           dX, dW, db, 0, 0, 0, flags, ws)
     torch.cuda.synchronize()
     gnn.gnn_workspace_status(ws)
     return (None if dX is None else dX.cpu().numpy()), dW.cpu().numpy(), (None if db is None else db.cpu().numpy())
@@ -132,3 +132,31 @@ def test_config5_one_gin_layer_backward_full_size():
     assert_parity(dX, rX, sX, "config 5 dX")
     assert_parity(dW, rW, sW, "config 5 dW")
     assert_parity(db, rb, sb, "config 5 db")
+
+
+@pytest.mark.parametrize("kind", ["gcn", "gin"])
+def test_deterministic_backward_is_bitwise_reproducible(kind):
+    rp, ci = _graph("rmat")
+    n = rp.size - 1
+    K, M = 64, 32
+    X = features(n, K, seed=11)
+    W = glorot(K, M, seed=12)
+    dY = features(n, M, seed=13)
+    if kind == "gcn":
+        ew = np.random.default_rng(14).uniform(0.1, 1.0, ci.size).astype(np.float32)
+        Y = oracle.gcn_layer(rp, ci, ew, X, W, None, True)
+        (rX, rW, rb), (sX, sW, sb) = oracle.gcn_layer_backward(rp, ci, ew, X, W, True, Y, dY, want_abs=True)
+        runs = [_run_backward(gnn.GNN_GCN, rp, ci, ew, 0.0, X, W, True, Y, dY, flags=gnn.GNN_FLAG_DETERMINISTIC)
+                for _ in range(3)]
+    else:
+        A = oracle.aggregate_gin(rp, ci, 0.0, X)
+        Y = oracle.gemm_bias_act(A, W, None, True)
+        (rX, rW, rb), (sX, sW, sb) = oracle.gin_layer_backward(rp, ci, 0.0, A, W, True, Y, dY, want_abs=True)
+        runs = [_run_backward(gnn.GNN_GIN, rp, ci, None, 0.0, A, W, True, Y, dY, flags=gnn.GNN_FLAG_DETERMINISTIC)
+                for _ in range(3)]
+    assert_parity(runs[0][0], rX, sX, f"deterministic {kind} dX")
+    assert_parity(runs[0][1], rW, sW, f"deterministic {kind} dW")
+    assert_parity(runs[0][2], rb, sb, f"deterministic {kind} db")
+    for r in runs[1:]:
+        for a, b in zip(runs[0], r):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
