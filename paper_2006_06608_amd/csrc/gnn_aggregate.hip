@@ -13,22 +13,18 @@
 // registers.  Other nodes are accumulated in the block's LDS slots laid out as Algorithm 1
 // prescribes; after a barrier the leader team of each slot writes the row: a plain store when
 // the block saw all groups of the node, one global atomic add per element otherwise (only nodes
-// whose groups span several blocks, i.e. high-degree ones).  Rows that receive atomics, and rows
-// without any entry, are initialised by a small kernel that runs first.
+// whose groups span several blocks, i.e. high-degree ones).  Rows that receive atomics are zeroed
+// by a small kernel that runs first; rows without any entry are written by blocks appended to the
+// grid of the main kernel.  GIN's own-row term enters the sum with the first group of each node.
+//
+// Deterministic mode.  No float atomics: the waves of a block add to a slot in wave order, a block
+// stores the partial rows of its (at most two) unfinished nodes to scratch rows, and a second
+// kernel adds the partial rows of every spanning node in block order.
 #include <hip/hip_runtime.h>
 
-#include "gnn_agg_common.h"
+#include "gnn_launch.h"
 
 namespace gnn {
-
-int partition_build_impl(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t ngs, void *workspace,
-                         size_t workspace_bytes, hipStream_t s);
-size_t pipe_lds_bytes(int T, int dim, int ngs, int dwl_log2, int wpb, bool weighted);
-int try_gin_layer_fused(AggParams &p, int vec, int wpb, const float *W, const float *b, float *out, int M, int relu,
-                        int64_t tiles_upper, bool force, hipStream_t s);
-int pipe_blocks(int vec, int iter, bool weighted, bool self, int cus, int wpb, size_t lds, int64_t tiles_upper, int n);
-int launch_aggregate_pipe(int vec, int iter, bool weighted, bool self, int blocks, int wpb, size_t lds, hipStream_t s,
-                          AggParams &p);
 
 // The workspace does not hold the partition the launch was prepared for: record why nothing was
 // computed (one thread).

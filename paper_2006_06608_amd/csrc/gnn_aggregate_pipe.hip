@@ -13,6 +13,7 @@
 // waves) and 64/dwl * ngs <= 64 * kPipeIdxLoads (a wave's index range fits the prefetch registers).
 #include <hip/hip_runtime.h>
 
+#include "gnn_launch.h"
 #include "gnn_pipe_common.h"
 
 namespace gnn {

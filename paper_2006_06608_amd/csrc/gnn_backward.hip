@@ -4,16 +4,9 @@
 // gradients over the transposed graph.
 #include <hip/hip_runtime.h>
 
-#include "gnn_internal.h"
+#include "gnn_launch.h"
 
 namespace gnn {
-
-int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
-                   const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
-                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes,
-                   size_t ws_reserved, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse);
-int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b, int relu,
-                     float *out, hipStream_t s);
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 

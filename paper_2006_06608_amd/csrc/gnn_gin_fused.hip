@@ -20,12 +20,10 @@
 // barrier of tile i+1 and refilled during tile i+3, so one barrier per tile still suffices.
 #include <hip/hip_runtime.h>
 
+#include "gnn_launch.h"
 #include "gnn_pipe_common.h"
 
 namespace gnn {
-
-void launch_agg_init(const AggParams &p, bool self, hipStream_t s);
-void launch_agg_epilogue_spanning(const AggParams &p, hipStream_t s);
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 

@@ -1,0 +1,46 @@
+// Host-side functions that the translation units of the library call in each other (HIP types,
+// hence separate from gnn_internal.h, which the plain C++ host file includes too).
+#ifndef GNN_LAUNCH_H
+#define GNN_LAUNCH_H
+
+#include <hip/hip_runtime.h>
+
+#include "gnn_agg_common.h"
+
+namespace gnn {
+
+// gnn_partition.hip: neighbor partitioning of rowptr into the workspace (Sec. 4.1).
+int partition_build_impl(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t ngs, void *workspace,
+                         size_t workspace_bytes, hipStream_t s);
+
+// gnn_aggregate.hip: shared implementation of gnn_aggregate_gcn / gnn_aggregate_gin and of the
+// aggregation step of the layer entry points.  self: add self_scale * X[i] (GIN).  bias/relu: fused
+// epilogue.  ws_reserved: bytes at the front of the workspace that the caller uses itself (0: only
+// the partition); the scratch of the deterministic mode is placed behind them.  ev_start/ev_stop
+// (may be null) are recorded around the main kernel.  fuse (may be null): see FuseSpec.
+int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                   const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
+                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes,
+                   size_t ws_reserved, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse);
+void launch_agg_init(const AggParams &p, bool self, hipStream_t s);
+void launch_agg_epilogue_spanning(const AggParams &p, hipStream_t s);
+
+// gnn_aggregate_pipe.hip: the persistent, software-pipelined kernel.  pipe_lds_bytes returns 0 when
+// the shape does not qualify; pipe_blocks returns the number of resident blocks to launch (0: do not
+// use the kernel, < 0: error).
+size_t pipe_lds_bytes(int T, int dim, int ngs, int dwl_log2, int wpb, bool weighted);
+int pipe_blocks(int vec, int iter, bool weighted, bool self, int cus, int wpb, size_t lds, int64_t tiles_upper, int n);
+int launch_aggregate_pipe(int vec, int iter, bool weighted, bool self, int blocks, int wpb, size_t lds, hipStream_t s,
+                          AggParams &p);
+
+// gnn_gin_fused.hip: GIN aggregation with the Update fused in.  Returns GNN_OK when the fused kernel
+// was launched, 1 when the shape does not qualify (nothing launched), < 0 on error.
+int try_gin_layer_fused(AggParams &p, int vec, int wpb, const float *W, const float *b, float *out, int M, int relu,
+                        int64_t tiles_upper, bool force, hipStream_t s);
+
+// gnn_update.hip: out[n,M] = act(A[n,K] W[K,M] + b) on the MFMA units.
+int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b, int relu,
+                     float *out, hipStream_t s);
+
+}  // namespace gnn
+#endif

@@ -6,7 +6,7 @@
 #include <vector>
 
 #include "gnn_device.h"
-#include "gnn_internal.h"
+#include "gnn_launch.h"
 
 namespace gnn {
 
