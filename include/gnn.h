@@ -63,19 +63,27 @@ extern "C" {
                                        hold (a block serves <= 64 groups, a wave <= 512 index entries);
                                        without either flag the library pipelines when ngs <= 8, where the
                                        per-tile latency chain dominates */
-#define GNN_FLAG_DETERMINISTIC 32u  /* bitwise identical results from run to run (for fixed ngs, dw, waves):
-                                       no float atomics.  The waves of a block add to a shared slot in wave
-                                       order; blocks leave the partial rows of nodes that span blocks in
-                                       scratch memory behind the caller's use of the workspace, and a second
-                                       kernel adds them in block order.  Needs a workspace sized by
-                                       gnn_workspace_bytes with max_dim >= dim (GNN_EWORKSPACE otherwise;
-                                       the size allows for blocks of >= 16 groups, which the automatic
-                                       waves_per_block guarantees); the general kernel is always used; not
-                                       combinable with GNN_FLAG_NO_BLOCK_OPT (GNN_EINVAL) */
+#define GNN_FLAG_DETERMINISTIC 32u  /* require the ordered flush (bitwise identical results from run to run
+                                       for fixed ngs, dw, waves): no float atomics.  The waves of a block add
+                                       to a shared slot in wave order; a block leaves the partial rows of nodes
+                                       that span blocks in scratch memory behind the caller's use of the
+                                       workspace, and the block that arrives last at such a node adds its
+                                       partial rows in block order.  One launch, nothing to zero.  The library
+                                       uses this flush by itself whenever the workspace has room for the
+                                       partial rows (sized by gnn_workspace_bytes with max_dim >= dim; the
+                                       size allows for blocks of >= 16 groups); with the flag a workspace
+                                       without room is an error (GNN_EWORKSPACE) and the general kernel is
+                                       always used.  Not combinable with GNN_FLAG_NO_BLOCK_OPT or
+                                       GNN_FLAG_ATOMIC_FLUSH (GNN_EINVAL) */
 #define GNN_FLAG_FUSION 64u         /* gnn_layer_forward(GNN_GIN): fuse the Update GEMM into the aggregation
                                        kernel where the shape allows (in_dim <= 128 and a multiple of 4,
                                        out_dim <= 64, <= 4 waves per block).  Opt-in: on the R-MAT
                                        configuration it is slower than the two separate kernels */
+
+#define GNN_FLAG_ATOMIC_FLUSH 128u  /* always finish nodes that span blocks the way Sec. 5.2 describes: the
+                                       leader adds the block's partial row to global memory with one float
+                                       atomic per element (rows zeroed by a kernel that runs first, bias and
+                                       activation of those rows by a kernel that runs last) */
 
 /* ================================================================================== */
 /* HOST-side preparation                                                              */

@@ -10,7 +10,7 @@ import numpy as np
 __all__ = [
     "GnnError", "lib_path", "load", "exported_symbols",
     "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_XCD_RUNS", "GNN_FLAG_NO_PIPELINE",
-    "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION",
+    "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
@@ -23,6 +23,7 @@ GNN_FLAG_REUSE_PARTITION, GNN_FLAG_NO_BLOCK_OPT, GNN_FLAG_XCD_RUNS, GNN_FLAG_NO_
 GNN_FLAG_PIPELINE = 16
 GNN_FLAG_DETERMINISTIC = 32
 GNN_FLAG_FUSION = 64
+GNN_FLAG_ATOMIC_FLUSH = 128
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("GNN_MI355X_LIB") or os.path.join(_PKG, "libgnn_mi355x.so")

@@ -17,7 +17,8 @@ struct AggParams {
     const float *ew;
     const float *X;
     float *out;
-    float *det_part;    // deterministic mode: float[2 * tiles * dim] partial rows of spanning nodes; else null
+    float *det_part;    // ordered flush: float[2 * tiles * dim] partial rows of spanning nodes; else null
+    int *cnt;           // ordered flush: per-node arrival counters (zero on entry and on exit)
     const float *bias;  // epilogue: out = act(sum + bias); may be null
     float self_scale;   // 1 + eps (GIN)
     int relu;
@@ -59,6 +60,24 @@ __device__ __forceinline__ void store_vec(float *p, const float (&r)[VEC])
     } else {
         *p = r[0];
     }
+}
+
+// Partial rows of the ordered flush travel between blocks that may run on different XCDs, whose L2
+// caches are not coherent with each other for ordinary accesses.  They are therefore written and
+// read with device-scope relaxed atomic accesses (write-through stores, cache-missing loads): no
+// cache-wide write-back or invalidate is needed, only the order store -> counter -> load.
+template <int VEC>
+__device__ __forceinline__ void store_vec_coherent(float *p, const float (&r)[VEC])
+{
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) __hip_atomic_store(p + j, r[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int VEC>
+__device__ __forceinline__ void load_vec_coherent(float (&r)[VEC], const float *p)
+{
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) r[j] = __hip_atomic_load(p + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 #ifndef GNN_NT_STORE

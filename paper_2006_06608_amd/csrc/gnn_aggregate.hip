@@ -12,14 +12,18 @@
 // (segmented reduction).  A node whose groups all sit in one wave is then stored straight from
 // registers.  Other nodes are accumulated in the block's LDS slots laid out as Algorithm 1
 // prescribes; after a barrier the leader team of each slot writes the row: a plain store when
-// the block saw all groups of the node, one global atomic add per element otherwise (only nodes
-// whose groups span several blocks, i.e. high-degree ones).  Rows that receive atomics are zeroed
-// by a small kernel that runs first; rows without any entry are written by blocks appended to the
-// grid of the main kernel.  GIN's own-row term enters the sum with the first group of each node.
-//
-// Deterministic mode.  No float atomics: the waves of a block add to a slot in wave order, a block
-// stores the partial rows of its (at most two) unfinished nodes to scratch rows, and a second
-// kernel adds the partial rows of every spanning node in block order.
+// the block saw all groups of the node.  Nodes whose groups span several blocks (high-degree ones)
+// are finished in one of two ways:
+//   * ordered flush (default when the workspace has room for partial rows): no float atomics.  The
+//     waves of a block add to a slot in wave order; the leader stores the block's partial row to
+//     scratch memory with device-coherent stores and counts itself in on the node's arrival counter;
+//     the block that arrives last adds the partial rows in block order, applies bias/activation and
+//     writes the row.  One launch, bitwise reproducible.
+//   * atomic flush (Sec. 5.2 as printed; GNN_FLAG_ATOMIC_FLUSH or no room): the leader adds its
+//     partial row to global memory with one float atomic per element; those rows are zeroed by a
+//     small kernel that runs first and get bias/activation from one that runs last.
+// Rows without any entry are written by blocks appended to the grid of the main kernel.  GIN's
+// own-row term enters the sum with the first group of each node.
 #include <hip/hip_runtime.h>
 
 #include "gnn_launch.h"
@@ -111,7 +115,11 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const WsHeader *hdr = p.hdr;
-    if (!header_ok(hdr, p)) return;
+    if (!header_ok(hdr, p)) {
+        // with the ordered flush no kernel runs before this one: record why nothing was computed
+        if (p.det_part && blockIdx.x == 0 && threadIdx.x == 0) note_stale(p.hdr, p);
+        return;
+    }
 
     const int T = p.T;
     if ((int64_t)blockIdx.x >= p.tile_blocks) {
@@ -318,6 +326,9 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
         const bool complete = first && s_last[slot] != 0;
         const float *srow = s_slot + (size_t)slot * dim;
         float *orow = p.out + (size_t)e.node * dim;
+        // ordered flush: the node of the block's first group goes to partial row 0 of the tile, any
+        // other unfinished node (it can only be the node of the last group) to partial row 1
+        float *prow = p.det_part ? p.det_part + ((size_t)tile * 2 + (lay.team == 0 ? 0 : 1)) * dim : nullptr;
         for (int c = 0; c < p.iter_total; ++c) {
             const int d = (c * dwl + tlane) * VEC;
             if (d >= dim) break;
@@ -329,79 +340,57 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
                 for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
                 if (p.stream_out) store_vec_stream<VEC>(orow + d, r);
                 else store_vec<VEC>(orow + d, r);
-            } else if (p.det_part) {
-                // the node of the block's first group goes to partial row 0 of the tile, any other
-                // unfinished node (it can only be the node of the last group) to partial row 1
-                store_vec<VEC>(p.det_part + ((size_t)tile * 2 + (lay.team == 0 ? 0 : 1)) * dim + d, r);
+            } else if (prow) {
+                store_vec_coherent<VEC>(prow + d, r);
             } else {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) atomicAdd(&orow[d + j], r[j]);
             }
         }
-    }
-}
-
-// Deterministic mode, second pass: a node whose groups span the tiles b0..b1 is the sum of those
-// tiles' partial rows, added in tile order, then bias/activation.  One wave scans 64 nodes, lists
-// the spanning ones and lets its teams finish them side by side.
-template <int VEC>
-__global__ __launch_bounds__(256) void k_agg_det_finish(AggParams p)
-{
-    __shared__ int s_list[256];
-    if (!header_ok(p.hdr, p)) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) note_stale(p.hdr, p);
-        return;
-    }
-    const int lane = threadIdx.x & 63;
-    const int dwl = 1 << p.dwl_log2, G = 64 >> p.dwl_log2;
-    const int tlane = lane & (dwl - 1), team_in_wave = lane >> p.dwl_log2;
-    int *mylist = s_list + (threadIdx.x & ~63);
-    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int64_t v = wave * 64 + lane;
-    int c0 = 0, c1 = 0;
-    if (v < p.n) {
-        c0 = p.ngptr[v];
-        c1 = p.ngptr[v + 1];
-    }
-    const bool spans = c1 > c0 && c0 / p.T != (c1 - 1) / p.T;
-    const unsigned long long m = __ballot(spans);
-    if (m == 0ull) return;
-    const int cnt = __popcll(m);
-    if (spans) mylist[__popcll(m & ((1ull << lane) - 1ull))] = lane;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    const int dim = p.dim;
-    for (int k0 = 0; k0 < cnt; k0 += G) {
-        const int k = k0 + team_in_wave;
-        const int l = k < cnt ? mylist[k] : 0;
-        const int g0 = __shfl(c0, l), g1 = __shfl(c1, l);
-        if (k >= cnt) continue;
-        const int64_t b0 = g0 / p.T, b1 = (g1 - 1) / p.T;
-        float *row = p.out + (size_t)(wave * 64 + l) * dim;
-        for (int c = 0; c < p.iter_total; ++c) {
-            const int d = (c * dwl + tlane) * VEC;
-            if (d >= dim) break;
-            // in its first tile the node is the tile's first node only if it starts the tile
-            float sum[VEC];
-            load_vec<VEC>(sum, p.det_part + ((size_t)b0 * 2 + (g0 % p.T == 0 ? 0 : 1)) * dim + d);
-            for (int64_t b = b0 + 1; b <= b1; b += 4) {
-                float t[4][VEC];
+        if (!complete && prow) {
+            // The node spans the tiles b0..b1.  Every one of them publishes its partial row (the
+            // stores above have completed once the wait below returns), then counts itself in; the
+            // block that arrives last adds the partial rows in tile order, applies bias/activation
+            // and writes the row, so the result does not depend on timing.
+            // (a workgroup-scope fence alone does not wait for the write-through stores: the explicit
+            // wait keeps the counter from overtaking them on its way to another memory channel)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            int arrived = 0;
+            if (tlane == 0) arrived = atomicAdd(&p.cnt[e.node], 1);
+            arrived = __shfl(arrived, lane - tlane);
+            const int gfirst = p.ngptr[e.node], gend = p.ngptr[e.node + 1];
+            const int64_t b0 = gfirst / T, b1 = (gend - 1) / T;
+            if (arrived == (int)(b1 - b0)) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                if (tlane == 0) p.cnt[e.node] = 0;  // ready for the next call
+                // in its first tile the node is the tile's first node only if it starts the tile
+                const float *first_row = p.det_part + ((size_t)b0 * 2 + (gfirst % T == 0 ? 0 : 1)) * dim;
+                for (int c = 0; c < p.iter_total; ++c) {
+                    const int d = (c * dwl + tlane) * VEC;
+                    if (d >= dim) break;
+                    float sum[VEC];
+                    load_vec_coherent<VEC>(sum, first_row + d);
+                    for (int64_t b = b0 + 1; b <= b1; b += 4) {
+                        float t[4][VEC];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
+                        for (int q = 0; q < 4; ++q) {
 #pragma unroll
-                    for (int j = 0; j < VEC; ++j) t[q][j] = 0.0f;
-                    if (b + q <= b1) load_vec<VEC>(t[q], p.det_part + ((size_t)(b + q) * 2) * dim + d);
-                }
+                            for (int j = 0; j < VEC; ++j) t[q][j] = 0.0f;
+                            if (b + q <= b1) load_vec_coherent<VEC>(t[q], p.det_part + ((size_t)(b + q) * 2) * dim + d);
+                        }
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (b + q <= b1) {
+                        for (int q = 0; q < 4; ++q)
+                            if (b + q <= b1) {
 #pragma unroll
-                        for (int j = 0; j < VEC; ++j) sum[j] += t[q][j];
+                                for (int j = 0; j < VEC; ++j) sum[j] += t[q][j];
+                            }
                     }
-            }
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) sum[j] = epilogue(sum[j], p.bias, d + j, p.relu);
-            store_vec<VEC>(row + d, sum);
+                    for (int j = 0; j < VEC; ++j) sum[j] = epilogue(sum[j], p.bias, d + j, p.relu);
+                    store_vec<VEC>(orow + d, sum);
+                }
+            }
         }
     }
 }
@@ -496,7 +485,8 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     if (dw > 64 || (dw & (dw - 1)) != 0) return GNN_EINVAL;
     if (wpb > kMaxWavesPerBlock) return GNN_EINVAL;
     const bool det = (flags & GNN_FLAG_DETERMINISTIC) != 0;
-    if (det && (flags & GNN_FLAG_NO_BLOCK_OPT)) return GNN_EINVAL;
+    const bool atomic_flush = (flags & GNN_FLAG_ATOMIC_FLUSH) != 0;
+    if (det && ((flags & GNN_FLAG_NO_BLOCK_OPT) || atomic_flush)) return GNN_EINVAL;
     if (n == 0) return GNN_OK;
     const bool auto_wpb = wpb == 0;
 
@@ -524,6 +514,7 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     p.X = X;
     p.out = out;
     p.det_part = nullptr;
+    p.cnt = (int *)(ws + L.cnt);
     p.bias = bias;
     p.self_scale = self_scale;
     p.relu = relu;
@@ -574,12 +565,16 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     const int64_t init_blocks = ((int64_t)n + 255) / 256;
     const int iter = p.iter_total < 4 ? p.iter_total : 4;
 
-    if (det) {
+    // Ordered flush (one launch, no float atomics, no zeroing pass) whenever the workspace has room
+    // for the partial rows behind the caller's own use of it; the atomic flush of Sec. 5.2 otherwise
+    // or on request.
+    float *det_part = nullptr;
+    {
         size_t off = L.total > ws_reserved ? L.total : ws_reserved;
         off = align_up(off);
-        if (off + det_scratch_bytes(ng_cap, T, dim) > workspace_bytes) return GNN_EWORKSPACE;
-        p.det_part = (float *)(ws + off);
+        if (off + det_scratch_bytes(ng_cap, T, dim) <= workspace_bytes) det_part = (float *)(ws + off);
     }
+    if (det && !det_part) return GNN_EWORKSPACE;
 
     // GIN layer with the Update fused in (the caller falls back to separate kernels if not taken)
     if (fuse && (flags & GNN_FLAG_FUSION) && !det) {
@@ -597,6 +592,7 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
 
     // persistent, pipelined kernel whenever its requirements hold
     const bool want_pipe = !det && !(flags & GNN_FLAG_NO_PIPELINE) && ((flags & GNN_FLAG_PIPELINE) || ngs <= 8);
+    const bool ordered = det || (det_part != nullptr && !atomic_flush);
     const size_t plds = want_pipe ? pipe_lds_bytes(T, dim, ngs, dwl_log2, wpb, weighted) : 0;
     if (plds > 0 && plds <= kMaxLdsBytes) {
         int dev = 0, cus = 0;
@@ -630,9 +626,9 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     p.extra_blocks = (int)extra;
     if (grid + extra >= ((int64_t)1 << 31)) return GNN_ELIMIT;
 
-    // (the deterministic mode adds nothing to `out`, so no row needs zeroing)
-    if (det) {
-    } else if (self) hipLaunchKernelGGL(k_agg_init<true>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+    // (the ordered flush adds nothing to `out`, so no row needs zeroing and no pass follows)
+    if (ordered) p.det_part = det_part;
+    else if (self) hipLaunchKernelGGL(k_agg_init<true>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
     else hipLaunchKernelGGL(k_agg_init<false>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
 
     if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
@@ -643,11 +639,8 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
         else launch_vec<1>(iter, weighted, self, g, b, lds, s, p);
     }
     if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
-    if (det) {
-        if (vec == 4) hipLaunchKernelGGL(k_agg_det_finish<4>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
-        else if (vec == 2) hipLaunchKernelGGL(k_agg_det_finish<2>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL(k_agg_det_finish<1>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
-    } else if (bias || relu) hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
+    if (!ordered && (bias || relu))
+        hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
     GNN_HIP_TRY(hipGetLastError());
     return GNN_OK;
 }

@@ -40,6 +40,7 @@ struct alignas(16) NgEntry {
 struct WsLayout {
     size_t header;   // offset of WsHeader
     size_t ngptr;    // int32[n+1]: id of the first neighbor group of node v; [n] = num_ng
+    size_t cnt;      // int32[n]: arrival counters of the ordered flush; zero between calls
     size_t scan;     // int32[scan_blocks + 1]
     size_t ng;       // NgEntry[ng_capacity]
     size_t tmp;      // float[n * max_dim]
@@ -71,6 +72,8 @@ inline WsLayout ws_layout(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs_f
     off += align_up(sizeof(WsHeader));
     L.ngptr = off;
     off += align_up(sizeof(int32_t) * ((size_t)n + 1));
+    L.cnt = off;
+    off += align_up(sizeof(int32_t) * ((size_t)n + 1));
     L.scan = off;
     off += align_up(sizeof(int32_t) * ((size_t)L.scan_blocks + 1));
     L.ng = off;
@@ -81,9 +84,10 @@ inline WsLayout ws_layout(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs_f
     return L;
 }
 
-// Deterministic mode (GNN_FLAG_DETERMINISTIC): every block may leave up to two partial rows (the
-// node of its first and of its last neighbor group) in scratch memory behind the caller's own use
-// of the workspace.  The workspace-size functions allow for blocks of at least kDetMinTile groups.
+// Ordered flush (the default when the workspace has room, required by GNN_FLAG_DETERMINISTIC): every
+// block may leave up to two partial rows (the node of its first and of its last neighbor group) in
+// scratch memory behind the caller's own use of the workspace.  The workspace-size functions allow
+// for blocks of at least kDetMinTile groups.
 constexpr int kDetMinTile = 16;
 
 inline size_t det_scratch_bytes(int64_t ng_capacity, int tile, int32_t dim)

@@ -104,10 +104,11 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_tiles(int64_t tiles, int 
     }
 }
 
-// Pass 3: ngptr[v] = id of the first neighbor group of node v.
+// Pass 3: ngptr[v] = id of the first neighbor group of node v; the arrival counters of the ordered
+// flush start at zero.
 __global__ __launch_bounds__(kScanThreads) void k_fill_ngptr(int n, const int *__restrict__ rowptr, int ngs,
                                                              const int *__restrict__ tile_off, int *__restrict__ ngptr,
-                                                             const WsHeader *hdr)
+                                                             int *__restrict__ cnt, const WsHeader *hdr)
 {
     __shared__ int s_wave[kScanThreads / 64];
     if (hdr->status != GNN_OK) return;
@@ -128,7 +129,10 @@ __global__ __launch_bounds__(kScanThreads) void k_fill_ngptr(int n, const int *_
 #pragma unroll
     for (int k = 0; k < kScanPerThread; ++k) {
         const int64_t v = v0 + k;
-        if (v < n) ngptr[v] = run;
+        if (v < n) {
+            ngptr[v] = run;
+            cnt[v] = 0;
+        }
         run += c[k];
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) ngptr[n] = tile_off[gridDim.x];
@@ -219,6 +223,7 @@ int partition_build_impl(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t 
     char *ws = (char *)workspace;
     WsHeader *hdr = (WsHeader *)(ws + L.header);
     int *ngptr = (int *)(ws + L.ngptr);
+    int *cnt = (int *)(ws + L.cnt);
     int *scan = (int *)(ws + L.scan);
     NgEntry *ng = (NgEntry *)(ws + L.ng);
     // header starts from a clean status; the scan kernel fills the rest
@@ -231,7 +236,7 @@ int partition_build_impl(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t 
                        rowptr);
     if (tiles > 0) {
         hipLaunchKernelGGL(k_fill_ngptr, dim3((unsigned)tiles), dim3(kScanThreads), 0, s, n, rowptr, ngs, scan, ngptr,
-                           hdr);
+                           cnt, hdr);
         const int64_t blocks = (L.ng_capacity + 255) / 256;
         if (blocks > 0)
             hipLaunchKernelGGL(k_fill_groups, dim3((unsigned)blocks), dim3(256), 0, s, n, rowptr, ngs, ngptr, ng, hdr);

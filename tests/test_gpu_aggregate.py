@@ -273,7 +273,7 @@ def _random_graph(rng):
     return rp, ci
 
 
-@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("seed", range(60))
 def test_random_graphs_and_parameter_combinations(seed):
     rng = np.random.default_rng(1000 + seed)
     rp, ci = _random_graph(rng)
@@ -284,6 +284,7 @@ def test_random_graphs_and_parameter_combinations(seed):
     wpb = int(rng.choice([0, 1, 2, 3, 4, 8, 16]))
     flags = int(rng.choice([0, 0, gnn.GNN_FLAG_XCD_RUNS, gnn.GNN_FLAG_PIPELINE, gnn.GNN_FLAG_NO_PIPELINE,
                             gnn.GNN_FLAG_DETERMINISTIC, gnn.GNN_FLAG_DETERMINISTIC | gnn.GNN_FLAG_XCD_RUNS,
+                            gnn.GNN_FLAG_ATOMIC_FLUSH, gnn.GNN_FLAG_ATOMIC_FLUSH | gnn.GNN_FLAG_XCD_RUNS,
                             gnn.GNN_FLAG_NO_BLOCK_OPT]))
     X = features(n, dim, seed=seed)
     what = f"seed {seed}: n {n} nnz {nnz} dim {dim} ngs {ngs} dw {dw} wpb {wpb} flags {flags}"

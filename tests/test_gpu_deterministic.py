@@ -1,4 +1,6 @@
-"""GNN_FLAG_DETERMINISTIC: no float atomics, so repeated runs agree bit for bit; values still match the oracle."""
+"""The ordered flush (GNN_FLAG_DETERMINISTIC, and the default when the workspace has room): no float
+atomics, so repeated runs agree bit for bit; values still match the oracle.  GNN_FLAG_ATOMIC_FLUSH
+selects the atomic flush of Sec. 5.2 instead."""
 import numpy as np
 import pytest
 import torch
@@ -42,7 +44,8 @@ def test_repeated_runs_are_bitwise_identical_and_match_the_oracle(kind, dim, ngs
     ref, ab = oracle.aggregate_gcn(rp, ci, ew, X, want_abs=True)
     first = run_gcn(G, X, ngs=ngs, dw=dw, wpb=wpb, flags=DET, ws=ws)
     assert_parity(first, ref, ab, f"deterministic gcn {kind} dim {dim}")
-    run_gcn(G, X, ngs=ngs, dw=dw, wpb=wpb, ws=ws)  # a default (atomic) run in between leaves no trace
+    atomic = run_gcn(G, X, ngs=ngs, dw=dw, wpb=wpb, flags=gnn.GNN_FLAG_ATOMIC_FLUSH, ws=ws)  # leaves no trace
+    assert_parity(atomic, ref, ab, f"atomic flush gcn {kind} dim {dim}")
     for _ in range(3):
         again = run_gcn(G, X, ngs=ngs, dw=dw, wpb=wpb, flags=DET | gnn.GNN_FLAG_REUSE_PARTITION, ws=ws)
         assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
@@ -98,9 +101,28 @@ def test_deterministic_mode_argument_errors():
         gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, X, out, 16, 8, 0, 0, DET, small)
     assert e.value.code == -3  # GNN_EWORKSPACE
     ws = gnn.alloc_workspace(G.n, G.nnz, 16, 8)
-    with pytest.raises(gnn.GnnError) as e:
-        gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, X, out, 16, 8, 0, 0, DET | gnn.GNN_FLAG_NO_BLOCK_OPT, ws)
-    assert e.value.code == -1  # GNN_EINVAL
+    for other in (gnn.GNN_FLAG_NO_BLOCK_OPT, gnn.GNN_FLAG_ATOMIC_FLUSH):
+        with pytest.raises(gnn.GnnError) as e:
+            gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, X, out, 16, 8, 0, 0, DET | other, ws)
+        assert e.value.code == -1  # GNN_EINVAL
+
+
+def test_default_is_ordered_when_the_workspace_has_room_and_atomic_otherwise():
+    rp, ci = _graph("rmat")
+    n = rp.size - 1
+    X = features(n, 64, seed=21)
+    G = DeviceGraph(rp, ci)
+    ref, ab = oracle.aggregate_gin(rp, ci, 0.0, X, want_abs=True)
+    roomy = gnn.alloc_workspace(G.n, G.nnz, 64, 4)
+    first = run_gin(G, 0.0, X, ngs=4, ws=roomy, flags=gnn.GNN_FLAG_NO_PIPELINE)
+    assert_parity(first, ref, ab, "default with room")
+    required = run_gin(G, 0.0, X, ngs=4, ws=roomy, flags=gnn.GNN_FLAG_NO_PIPELINE | DET)
+    assert np.array_equal(first.view(np.uint32), required.view(np.uint32))  # same flush, same bits
+    for _ in range(3):
+        again = run_gin(G, 0.0, X, ngs=4, ws=roomy, flags=gnn.GNN_FLAG_NO_PIPELINE)
+        assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
+    tight = gnn.alloc_workspace(G.n, G.nnz, 0, 4)  # no rows for partial sums: the atomic flush serves
+    assert_parity(run_gin(G, 0.0, X, ngs=4, ws=tight), ref, ab, "default without room")
 
 
 def test_deterministic_full_size_rmat():
