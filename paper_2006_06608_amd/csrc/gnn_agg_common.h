@@ -122,7 +122,11 @@ __device__ __forceinline__ T load_stream(const T *p)
 
 __device__ __forceinline__ bool header_ok(const WsHeader *hdr, const AggParams &p)
 {
-    return hdr->magic == kMagic && hdr->status == GNN_OK && hdr->ngs == p.ngs && hdr->n == p.n && hdr->nnz == p.nnz;
+    // all fields are read at once (no short-circuit: one round trip instead of five)
+    const uint32_t magic = hdr->magic;
+    const int32_t n = hdr->n, ngs = hdr->ngs, status = hdr->status;
+    const int64_t nnz = hdr->nnz;
+    return (magic == kMagic) & (status == GNN_OK) & (ngs == p.ngs) & (n == p.n) & (nnz == p.nnz);
 }
 
 __device__ __forceinline__ float epilogue(float v, const float *bias, int d, int relu)
