@@ -77,6 +77,22 @@ def aggregate_gin(rowptr, colidx, eps: float, X, want_abs: bool = False):
     return (out, ab) if want_abs else out
 
 
+REDUCE_MAX, REDUCE_MIN, REDUCE_MEAN = 1, 2, 3
+
+
+def aggregate_reduce(rowptr, colidx, X, op: int, want_abs: bool = False):
+    """Sec. 3.1 aggregations over the neighbour embeddings alone: max, min or mean per feature;
+    rows without entries give 0."""
+    assert op in (REDUCE_MAX, REDUCE_MIN, REDUCE_MEAN)
+    rowptr, colidx, X = _i32(rowptr), _i32(colidx), _f32(X)
+    n, dim = rowptr.size - 1, X.shape[1]
+    out = np.empty((n, dim), dtype=np.float32)
+    ab = np.empty((n, dim), dtype=np.float64) if want_abs else None
+    _L().orc_aggregate_reduce(ctypes.c_int32(n), _p(rowptr), _p(colidx), _p(X), ctypes.c_int32(dim),
+                              ctypes.c_int32(op), _p(out), _p(ab))
+    return (out, ab) if want_abs else out
+
+
 def gemm_bias_act(A, W, b=None, relu: bool = False, want_abs: bool = False):
     """Update phase: act(A @ W + b)."""
     A, W = _f32(A), _f32(W)

@@ -16,7 +16,9 @@
  * neighbor-group example of Sec. 4.1, the invariants of Algorithm 1, the
  * literal values of Eq. 5 / Eq. 6, hand-computed AES values and thresholds,
  * and structural properties of the renumbering (bijection, cliques become
- * contiguous, AES falls on shuffled block-diagonal graphs, one hand trace).
+ * contiguous, AES falls on shuffled block-diagonal graphs, one hand trace);
+ * max / min / mean: numpy reductions over dense neighbour lists on tiny graphs,
+ * closed forms on paths and stars, min <= mean <= max, mean = sum / degree.
  * Parity unpinned: none of the functions below.
  */
 #include <math.h>
@@ -63,6 +65,37 @@ void orc_aggregate_gin(int32_t n, const int32_t *rowptr, const int32_t *colidx, 
             }
             out[(size_t)i * dim + k] = (float)acc;
             if (abs_out) abs_out[(size_t)i * dim + k] = aacc;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ Sec. 3.1: other neighbour aggregations
+ * The paper names sum and min as examples of aggregation over the neighbour embeddings only; mean
+ * and max are the other two reductions GNN layers use.  No self term, no weights.
+ * op 1: out[i,k] = max_j X[j,k];  op 2: min;  op 3: mean = (sum_j X[j,k]) / deg(i), summed in double.
+ * A row without entries gives 0 (there is nothing to reduce; 0 is what a sum gives).  Duplicate
+ * entries count as often as they are stored (mean), and do not matter for max/min.
+ * abs_out (op 3 only, may be NULL): sum |x| / deg, the error scale of the mean. */
+void orc_aggregate_reduce(int32_t n, const int32_t *rowptr, const int32_t *colidx, const float *X, int32_t dim,
+                          int32_t op, float *out, double *abs_out)
+{
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t deg = rowptr[i + 1] - rowptr[i];
+        for (int32_t k = 0; k < dim; ++k) {
+            float best = 0.0f;
+            double acc = 0.0, aacc = 0.0;
+            for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+                const float x = X[(size_t)colidx[e] * dim + k];
+                if (e == rowptr[i]) best = x;
+                else if (op == 1 && x > best) best = x;
+                else if (op == 2 && x < best) best = x;
+                acc += (double)x;
+                aacc += fabs((double)x);
+            }
+            float r = best;
+            if (op == 3) r = deg > 0 ? (float)(acc / (double)deg) : 0.0f;
+            out[(size_t)i * dim + k] = r;
+            if (abs_out) abs_out[(size_t)i * dim + k] = deg > 0 ? aacc / (double)deg : 0.0;
         }
     }
 }
