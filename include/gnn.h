@@ -186,6 +186,22 @@ int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32
                       int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
                       void *stream);
 
+/* Aggregation over the neighbour embeddings alone with another reduction (Sec. 3.1 names sum and
+ * min as examples): out[i,:] = reduce over the stored entries j of row i of X[j,:], no weights, no
+ * self term.  op: GNN_REDUCE_SUM, GNN_REDUCE_MAX, GNN_REDUCE_MIN (elementwise, exact) or
+ * GNN_REDUCE_MEAN (sum divided by the row length).  A row without entries gives 0.  Max, min and mean
+ * use the ordered flush, so the workspace must be sized with max_dim >= dim (GNN_EWORKSPACE otherwise)
+ * and the flags GNN_FLAG_NO_BLOCK_OPT, _ATOMIC_FLUSH, _PIPELINE, _FUSION are refused (GNN_EINVAL).
+ * Everything else as for gnn_aggregate_gcn. */
+#define GNN_REDUCE_SUM 0
+#define GNN_REDUCE_MAX 1
+#define GNN_REDUCE_MIN 2
+#define GNN_REDUCE_MEAN 3
+int gnn_aggregate_reduce(int op, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                         const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw,
+                         int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
+                         void *stream);
+
 /* Update phase alone (Sec. 2.1, w.a + b): out[n,M] = act(A[n,K] W[K,M] + b), fp32 MFMA.
  * b NULL or float[M]; relu 0/1.  DEVICE pointers. */
 int gnn_update_gemm(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b,

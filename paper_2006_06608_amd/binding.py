@@ -10,7 +10,8 @@ import numpy as np
 __all__ = [
     "GnnError", "lib_path", "load", "exported_symbols",
     "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_XCD_RUNS", "GNN_FLAG_NO_PIPELINE",
-    "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH",
+    "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
+    "GNN_REDUCE_MEAN", "gnn_aggregate_reduce",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
@@ -24,6 +25,7 @@ GNN_FLAG_PIPELINE = 16
 GNN_FLAG_DETERMINISTIC = 32
 GNN_FLAG_FUSION = 64
 GNN_FLAG_ATOMIC_FLUSH = 128
+GNN_REDUCE_SUM, GNN_REDUCE_MAX, GNN_REDUCE_MIN, GNN_REDUCE_MEAN = 0, 1, 2, 3
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("GNN_MI355X_LIB") or os.path.join(_PKG, "libgnn_mi355x.so")
@@ -33,6 +35,7 @@ _SYMBOLS = [
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
+    "gnn_aggregate_reduce",
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
     "gnn_last_hip_error", "gnn_version", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
 ]
@@ -274,6 +277,16 @@ def gnn_aggregate_gin(n, nnz, rowptr, colidx, eps, X, out, dim, ngs=0, dw=0, wav
                                   _f32(eps), _dev(X, "float32", "X"), _dev(out, "float32", "out"), _i32(dim),
                                   _i32(ngs), _i32(dw), _i32(waves_per_block), _u32(flags), wp, wb, _stream(stream))
     _check(rc, "gnn_aggregate_gin")
+
+
+def gnn_aggregate_reduce(op, n, nnz, rowptr, colidx, X, out, dim, ngs=0, dw=0, waves_per_block=0, flags=0,
+                         workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    rc = load().gnn_aggregate_reduce(ctypes.c_int(op), _i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"),
+                                     _dev(colidx, "int32", "colidx"), _dev(X, "float32", "X"),
+                                     _dev(out, "float32", "out"), _i32(dim), _i32(ngs), _i32(dw),
+                                     _i32(waves_per_block), _u32(flags), wp, wb, _stream(stream))
+    _check(rc, "gnn_aggregate_reduce")
 
 
 def gnn_update_gemm(n, K, M, A, W, b, relu, out, stream=None):

@@ -20,6 +20,7 @@ struct AggParams {
     float *det_part;    // ordered flush: float[2 * tiles * dim] partial rows of spanning nodes; else null
     int *cnt;           // ordered flush: per-node arrival counters (zero on entry and on exit)
     const float *bias;  // epilogue: out = act(sum + bias); may be null
+    const int *rowptr;  // mean aggregation: a finished row is divided by its length; null otherwise
     float self_scale;   // 1 + eps (GIN)
     int relu;
     int n;
@@ -35,6 +36,26 @@ struct AggParams {
     int64_t tile_blocks;  // one-block-per-tile kernel: blocks that serve tiles
     int64_t nnz;
 };
+
+// Reduction over the neighbour rows (Sec. 3.1): sum (GCN, GIN; mean is a sum scaled when the row is
+// written), or an elementwise max / min.
+constexpr int kOpSum = 0, kOpMax = 1, kOpMin = 2;
+
+template <int OP>
+__device__ __forceinline__ float op_identity()
+{
+    if constexpr (OP == kOpMax) return -__builtin_inff();
+    else if constexpr (OP == kOpMin) return __builtin_inff();
+    else return 0.0f;
+}
+
+template <int OP>
+__device__ __forceinline__ float op_combine(float a, float b)
+{
+    if constexpr (OP == kOpMax) return fmaxf(a, b);
+    else if constexpr (OP == kOpMin) return fminf(a, b);
+    else return a + b;
+}
 
 template <int VEC>
 __device__ __forceinline__ void load_vec(float (&r)[VEC], const float *p)
@@ -127,6 +148,13 @@ __device__ __forceinline__ bool header_ok(const WsHeader *hdr, const AggParams &
     const int32_t n = hdr->n, ngs = hdr->ngs, status = hdr->status;
     const int64_t nnz = hdr->nnz;
     return (magic == kMagic) & (status == GNN_OK) & (ngs == p.ngs) & (n == p.n) & (nnz == p.nnz);
+}
+
+// 1 / (row length) for the mean aggregation, 1 otherwise.
+__device__ __forceinline__ float row_scale(const AggParams &p, int node)
+{
+    if (!p.rowptr) return 1.0f;
+    return 1.0f / (float)(p.rowptr[node + 1] - p.rowptr[node]);
 }
 
 __device__ __forceinline__ float epilogue(float v, const float *bias, int d, int relu)

@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256) void k_agg_epilogue_spanning(AggParams p)
 #endif
 constexpr int kXcdRun = GNN_XCD_RUN;  // consecutive tiles that stay on one XCD
 
-template <int VEC, int ITER, int U, bool WEIGHTED, bool SELF>
+template <int VEC, int ITER, int U, bool WEIGHTED, bool SELF, int OP>
 __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
         s_col[i] = load_stream(&p.colidx[e0 + i]);
         if (WEIGHTED) s_w[i] = load_stream(&p.ew[e0 + i]);
     }
-    for (int i = tid; i < T * dim; i += blockDim.x) s_slot[i] = 0.0f;
+    for (int i = tid; i < T * dim; i += blockDim.x) s_slot[i] = op_identity<OP>();
     for (int i = tid; i < T; i += blockDim.x) s_last[i] = 0;
     __syncthreads();
     const int slot = block_layout_slot(lay, dwl_log2, s_wave_cnt);
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
         for (int c = 0; c < ITER; ++c) {
             dok[c] = ((c0 + c) * dwl + tlane) * VEC < dim;
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) acc[c][j] = 0.0f;
+            for (int j = 0; j < VEC; ++j) acc[c][j] = op_identity<OP>();
             // GIN: the node's own row enters the sum with the first group of the node, as one more
             // term, so its load overlaps with the neighbour loads instead of following them
             if (SELF && first && len > 0 && dok[c]) {
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
                         load_vec<VEC>(v[u][c], xb + (size_t)(unsigned)col[u] * (unsigned)dim + (size_t)c * dwl * VEC);
                     } else {
 #pragma unroll
-                        for (int j = 0; j < VEC; ++j) v[u][c][j] = 0.0f;
+                        for (int j = 0; j < VEC; ++j) v[u][c][j] = op_identity<OP>();
                     }
                 }
             }
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) {
                         if (WEIGHTED) acc[c][j] = fmaf(w[u], v[u][c][j], acc[c][j]);
-                        else acc[c][j] += v[u][c][j];
+                        else acc[c][j] = op_combine<OP>(acc[c][j], v[u][c][j]);
                     }
         }
 
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) {
                         const float ov = __shfl_down(acc[c][j], o);
-                        if (take) acc[c][j] += ov;
+                        if (take) acc[c][j] = op_combine<OP>(acc[c][j], ov);
                     }
                 if (!lastflag_done) {
                     const int ol = __shfl_down(lastflag, o);
@@ -272,13 +272,14 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
         if (seg_head) {
             if (complete_in_wave) {
                 // all groups of the node sat in this wave: store from registers
+                const float rs = row_scale(p, e.node);
 #pragma unroll
                 for (int c = 0; c < ITER; ++c) {
                     const int d = ((c0 + c) * dwl + tlane) * VEC;
                     if (d < dim) {
                         float r[VEC];
 #pragma unroll
-                        for (int j = 0; j < VEC; ++j) r[j] = epilogue(acc[c][j], p.bias, d + j, p.relu);
+                        for (int j = 0; j < VEC; ++j) r[j] = epilogue(acc[c][j] * rs, p.bias, d + j, p.relu);
                         if (p.stream_out) store_vec_stream<VEC>(p.out + (size_t)e.node * dim + d, r);
                         else store_vec<VEC>(p.out + (size_t)e.node * dim + d, r);
                     }
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
                         const int d = ((c0 + c) * dwl + tlane) * VEC;
                         if (d < dim) {
 #pragma unroll
-                            for (int j = 0; j < VEC; ++j) srow[d + j] += acc[c][j];
+                            for (int j = 0; j < VEC; ++j) srow[d + j] = op_combine<OP>(srow[d + j], acc[c][j]);
                         }
                     }
                     if (lastflag != 0 && tlane == 0) s_last[slot] = 1;
@@ -336,8 +337,9 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 #pragma unroll
             for (int j = 0; j < VEC; ++j) r[j] = srow[d + j];
             if (complete) {
+                const float rs = row_scale(p, e.node);
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j], p.bias, d + j, p.relu);
+                for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j] * rs, p.bias, d + j, p.relu);
                 if (p.stream_out) store_vec_stream<VEC>(orow + d, r);
                 else store_vec<VEC>(orow + d, r);
             } else if (prow) {
@@ -376,18 +378,19 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
 #pragma unroll
-                            for (int j = 0; j < VEC; ++j) t[q][j] = 0.0f;
+                            for (int j = 0; j < VEC; ++j) t[q][j] = op_identity<OP>();
                             if (b + q <= b1) load_vec_coherent<VEC>(t[q], p.det_part + ((size_t)(b + q) * 2) * dim + d);
                         }
 #pragma unroll
                         for (int q = 0; q < 4; ++q)
                             if (b + q <= b1) {
 #pragma unroll
-                                for (int j = 0; j < VEC; ++j) sum[j] += t[q][j];
+                                for (int j = 0; j < VEC; ++j) sum[j] = op_combine<OP>(sum[j], t[q][j]);
                             }
                     }
+                    const float rs = row_scale(p, e.node);
 #pragma unroll
-                    for (int j = 0; j < VEC; ++j) sum[j] = epilogue(sum[j], p.bias, d + j, p.relu);
+                    for (int j = 0; j < VEC; ++j) sum[j] = epilogue(sum[j] * rs, p.bias, d + j, p.relu);
                     store_vec<VEC>(orow + d, sum);
                 }
             }
@@ -448,24 +451,27 @@ void launch_agg_epilogue_spanning(const AggParams &p, hipStream_t s)
 }
 
 template <int VEC, int ITER, int U>
-static void launch_main(bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s, const AggParams &p)
+static void launch_main(int op, bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s,
+                        const AggParams &p)
 {
-    if (self) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, true>), grid, block, lds, s, p);
-    else if (weighted) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, true, false>), grid, block, lds, s, p);
-    else hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, false>), grid, block, lds, s, p);
+    if (op == kOpMax) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, false, kOpMax>), grid, block, lds, s, p);
+    else if (op == kOpMin) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, false, kOpMin>), grid, block, lds, s, p);
+    else if (self) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, true, kOpSum>), grid, block, lds, s, p);
+    else if (weighted) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, true, false, kOpSum>), grid, block, lds, s, p);
+    else hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, false, kOpSum>), grid, block, lds, s, p);
 }
 
 template <int VEC>
-static void launch_vec(int iter, bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s,
+static void launch_vec(int op, int iter, bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s,
                        const AggParams &p)
 {
     // U neighbor rows in flight per lane, sized so that U*ITER*VEC stays near 32 registers
     constexpr int U1 = 8, U2 = VEC == 4 ? 4 : 8, U3 = 4, U4 = VEC == 4 ? 2 : 4;
     switch (iter) {
-        case 1: launch_main<VEC, 1, U1>(weighted, self, grid, block, lds, s, p); break;
-        case 2: launch_main<VEC, 2, U2>(weighted, self, grid, block, lds, s, p); break;
-        case 3: launch_main<VEC, 3, U3>(weighted, self, grid, block, lds, s, p); break;
-        default: launch_main<VEC, 4, U4>(weighted, self, grid, block, lds, s, p); break;
+        case 1: launch_main<VEC, 1, U1>(op, weighted, self, grid, block, lds, s, p); break;
+        case 2: launch_main<VEC, 2, U2>(op, weighted, self, grid, block, lds, s, p); break;
+        case 3: launch_main<VEC, 3, U3>(op, weighted, self, grid, block, lds, s, p); break;
+        default: launch_main<VEC, 4, U4>(op, weighted, self, grid, block, lds, s, p); break;
     }
 }
 
@@ -473,11 +479,18 @@ static void launch_vec(int iter, bool weighted, bool self, dim3 grid, dim3 block
 // gnn_layer_forward.  self: add self_scale * X[i] (GIN).  bias/relu: fused epilogue.  ws_reserved:
 // bytes at the front of the workspace that the caller uses itself (0: only the partition); the
 // scratch of the deterministic mode is placed behind them.
-int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
-                   const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
-                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes,
-                   size_t ws_reserved, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse)
+int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr,
+                          const int32_t *colidx, const float *ew, const float *X, float *out, int32_t dim, int32_t ngs,
+                          int32_t dw, int32_t wpb, uint32_t flags, const float *bias, int relu, void *workspace,
+                          size_t workspace_bytes, size_t ws_reserved, hipStream_t s, hipEvent_t ev_start,
+                          hipEvent_t ev_stop, FuseSpec *fuse)
 {
+    const bool plain_sum = op == kOpSum && !mean;
+    if (op != kOpSum && op != kOpMax && op != kOpMin) return GNN_EINVAL;
+    if (!plain_sum && (mean && op != kOpSum)) return GNN_EINVAL;
+    if (!plain_sum && (ew || self || fuse)) return GNN_EINVAL;
+    if (!plain_sum && (flags & (GNN_FLAG_NO_BLOCK_OPT | GNN_FLAG_ATOMIC_FLUSH | GNN_FLAG_PIPELINE | GNN_FLAG_FUSION)))
+        return GNN_EINVAL;
     if (n < 0 || nnz < 0 || nnz >= ((int64_t)1 << 31) || dim <= 0 || ngs < 0 || dw < 0 || wpb < 0) return GNN_EINVAL;
     if (!rowptr || (nnz > 0 && !colidx)) return GNN_EINVAL;
     if (n > 0 && (!X || !out)) return GNN_EINVAL;
@@ -516,6 +529,7 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     p.det_part = nullptr;
     p.cnt = (int *)(ws + L.cnt);
     p.bias = bias;
+    p.rowptr = mean ? rowptr : nullptr;
     p.self_scale = self_scale;
     p.relu = relu;
     p.n = n;
@@ -551,7 +565,7 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     }
 
     // the workspace-size functions allow deterministic scratch for blocks of kDetMinTile groups
-    if (det && auto_wpb)
+    if ((det || !plain_sum) && auto_wpb)
         while (wpb * (64 >> dwl_log2) < kDetMinTile && wpb < kMaxWavesPerBlock) wpb *= 2;
     const int T = wpb * (64 >> dwl_log2);
     p.T = T;
@@ -574,7 +588,7 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
         off = align_up(off);
         if (off + det_scratch_bytes(ng_cap, T, dim) <= workspace_bytes) det_part = (float *)(ws + off);
     }
-    if (det && !det_part) return GNN_EWORKSPACE;
+    if ((det || !plain_sum) && !det_part) return GNN_EWORKSPACE;
 
     // GIN layer with the Update fused in (the caller falls back to separate kernels if not taken)
     if (fuse && (flags & GNN_FLAG_FUSION) && !det) {
@@ -591,7 +605,8 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     }
 
     // persistent, pipelined kernel whenever its requirements hold
-    const bool want_pipe = !det && !(flags & GNN_FLAG_NO_PIPELINE) && ((flags & GNN_FLAG_PIPELINE) || ngs <= 8);
+    const bool want_pipe =
+        plain_sum && !det && !(flags & GNN_FLAG_NO_PIPELINE) && ((flags & GNN_FLAG_PIPELINE) || ngs <= 8);
     const bool ordered = det || (det_part != nullptr && !atomic_flush);
     const size_t plds = want_pipe ? pipe_lds_bytes(T, dim, ngs, dwl_log2, wpb, weighted) : 0;
     if (plds > 0 && plds <= kMaxLdsBytes) {
@@ -634,9 +649,9 @@ int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const in
     if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
     {
         const dim3 g((unsigned)(grid + extra)), b((unsigned)(wpb * 64));
-        if (vec == 4) launch_vec<4>(iter, weighted, self, g, b, lds, s, p);
-        else if (vec == 2) launch_vec<2>(iter, weighted, self, g, b, lds, s, p);
-        else launch_vec<1>(iter, weighted, self, g, b, lds, s, p);
+        if (vec == 4) launch_vec<4>(op, iter, weighted, self, g, b, lds, s, p);
+        else if (vec == 2) launch_vec<2>(op, iter, weighted, self, g, b, lds, s, p);
+        else launch_vec<1>(op, iter, weighted, self, g, b, lds, s, p);
     }
     if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
     if (!ordered && (bias || relu))
@@ -666,6 +681,24 @@ int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32
     return aggregate_impl(true, 1.0f + eps, n, nnz, rowptr, colidx, nullptr, X, out, dim, ngs, dw, waves_per_block,
                           flags, nullptr, 0, workspace, workspace_bytes, 0, (hipStream_t)stream, nullptr, nullptr,
                           nullptr);
+}
+
+int gnn_aggregate_reduce(int op, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *X,
+                         float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t waves_per_block, uint32_t flags,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    int kop = kOpSum;
+    bool mean = false;
+    switch (op) {
+        case GNN_REDUCE_SUM: break;
+        case GNN_REDUCE_MAX: kop = kOpMax; break;
+        case GNN_REDUCE_MIN: kop = kOpMin; break;
+        case GNN_REDUCE_MEAN: mean = true; break;
+        default: return GNN_EINVAL;
+    }
+    return aggregate_reduce_impl(kop, mean, false, 0.0f, n, nnz, rowptr, colidx, nullptr, X, out, dim, ngs, dw,
+                                 waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, 0, (hipStream_t)stream,
+                                 nullptr, nullptr, nullptr);
 }
 
 }  // extern "C"

@@ -18,10 +18,23 @@ int partition_build_impl(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t 
 // epilogue.  ws_reserved: bytes at the front of the workspace that the caller uses itself (0: only
 // the partition); the scratch of the deterministic mode is placed behind them.  ev_start/ev_stop
 // (may be null) are recorded around the main kernel.  fuse (may be null): see FuseSpec.
-int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
-                   const float *ew, const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t wpb,
-                   uint32_t flags, const float *bias, int relu, void *workspace, size_t workspace_bytes,
-                   size_t ws_reserved, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop, FuseSpec *fuse);
+// op: kOpSum / kOpMax / kOpMin; mean: divide every finished row by its length (op must be kOpSum).
+// Anything but the plain sum takes no weights, no self term, and needs the ordered flush.
+int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr,
+                          const int32_t *colidx, const float *ew, const float *X, float *out, int32_t dim, int32_t ngs,
+                          int32_t dw, int32_t wpb, uint32_t flags, const float *bias, int relu, void *workspace,
+                          size_t workspace_bytes, size_t ws_reserved, hipStream_t s, hipEvent_t ev_start,
+                          hipEvent_t ev_stop, FuseSpec *fuse);
+
+inline int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr,
+                          const int32_t *colidx, const float *ew, const float *X, float *out, int32_t dim, int32_t ngs,
+                          int32_t dw, int32_t wpb, uint32_t flags, const float *bias, int relu, void *workspace,
+                          size_t workspace_bytes, size_t ws_reserved, hipStream_t s, hipEvent_t ev_start,
+                          hipEvent_t ev_stop, FuseSpec *fuse)
+{
+    return aggregate_reduce_impl(kOpSum, false, self, self_scale, n, nnz, rowptr, colidx, ew, X, out, dim, ngs, dw, wpb,
+                                 flags, bias, relu, workspace, workspace_bytes, ws_reserved, s, ev_start, ev_stop, fuse);
+}
 void launch_agg_init(const AggParams &p, bool self, hipStream_t s);
 void launch_agg_epilogue_spanning(const AggParams &p, hipStream_t s);
 
