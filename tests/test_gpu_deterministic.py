@@ -138,3 +138,29 @@ def test_deterministic_full_size_rmat():
         assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
     ref, ab = oracle.aggregate_gin(g.rowptr, g.colidx, 0.0, X, want_abs=True)
     assert_parity(first, ref, ab, "deterministic config 5")
+
+
+def test_ordered_flush_on_two_streams_at_once():
+    """Two aggregations with their own workspaces run concurrently on two streams; each must give the
+    bits it gives alone (partial rows and arrival counters are per workspace)."""
+    g = config_graph(5, shrink=4)
+    n = g.n
+    G = DeviceGraph(g.rowptr, g.colidx)
+    Xa, Xb = dev(features(n, 64, seed=31)), dev(features(n, 64, seed=32))
+    wsa, wsb = gnn.alloc_workspace(G.n, G.nnz, 64, 0), gnn.alloc_workspace(G.n, G.nnz, 64, 0)
+    ref_a, ref_b = torch.empty_like(Xa), torch.empty_like(Xb)
+    gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, Xa, ref_a, 64, 0, 0, 0, DET, wsa)
+    gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, Xb, ref_b, 64, 0, 0, 0, DET, wsb)
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    outs_a = [torch.empty_like(Xa) for _ in range(6)]
+    outs_b = [torch.empty_like(Xb) for _ in range(6)]
+    reuse = DET | gnn.GNN_FLAG_REUSE_PARTITION
+    for oa, ob in zip(outs_a, outs_b):
+        gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, Xa, oa, 64, 0, 0, 0, reuse, wsa, sa)
+        gnn.gnn_aggregate_gin(G.n, G.nnz, G.rowptr, G.colidx, 0.0, Xb, ob, 64, 0, 0, 0, reuse, wsb, sb)
+    torch.cuda.synchronize()
+    for oa, ob in zip(outs_a, outs_b):
+        assert torch.equal(oa, ref_a) and torch.equal(ob, ref_b)
+    gnn.gnn_workspace_status(wsa)
+    gnn.gnn_workspace_status(wsb)
