@@ -228,6 +228,23 @@ int gnn_layer_forward_timed(int kind, int32_t n, int64_t nnz, const int32_t *row
                             int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
                             void *stream, void *ev_agg_start, void *ev_agg_stop);
 
+/* A whole model in one call (the evaluation settings of Sec. 7.1: GCN 2 layers, GIN 5 layers):
+ * num_layers calls of gnn_layer_forward chained, ReLU after every layer but the last, the neighbor
+ * partition built once (or reused with GNN_FLAG_REUSE_PARTITION).  dims: HOST int32[num_layers+1],
+ * layer l maps dims[l] -> dims[l+1].  W: HOST array of num_layers DEVICE pointers (W[l] is
+ * float[dims[l]*dims[l+1]]); b: NULL, or a HOST array of num_layers DEVICE pointers or NULLs.
+ * X float[n*dims[0]], out float[n*dims[num_layers]] (DEVICE).  The hidden activations live in the
+ * workspace, which gnn_model_workspace_bytes sizes (layer workspace + two activation buffers).
+ * ev_agg_start / ev_agg_stop: NULL, or HOST arrays of num_layers hipEvent_t (entries may be NULL)
+ * recorded around the aggregation kernel of each layer, as in gnn_layer_forward_timed.
+ * Only enqueues; the host arrays are read before the call returns. */
+size_t gnn_model_workspace_bytes(int32_t n, int64_t nnz, int32_t num_layers, const int32_t *dims, int32_t ngs);
+int gnn_model_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                      const float *ew, float eps, const float *X, int32_t num_layers, const int32_t *dims,
+                      const float *const *W, const float *const *b, float *out, int32_t ngs, int32_t dw,
+                      int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
+                      void *stream, void *const *ev_agg_start, void *const *ev_agg_stop);
+
 /* Backward pass of gnn_layer_forward (training; the aggregation kernel is reused on gradients,
  * Sec. 7.2).  rowptr_t / colidx_t / ew_t: the TRANSPOSED graph (gnn_csr_transpose; a symmetric graph
  * with symmetric weights is its own transpose), and `workspace` holds ITS partition.

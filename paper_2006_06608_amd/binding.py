@@ -3,7 +3,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Optional, Tuple
+from typing import Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -11,7 +11,7 @@ __all__ = [
     "GnnError", "lib_path", "load", "exported_symbols",
     "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_XCD_RUNS", "GNN_FLAG_NO_PIPELINE",
     "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
-    "GNN_REDUCE_MEAN", "gnn_aggregate_reduce",
+    "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
@@ -35,7 +35,7 @@ _SYMBOLS = [
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
-    "gnn_aggregate_reduce",
+    "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward",
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
     "gnn_last_hip_error", "gnn_version", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
 ]
@@ -69,6 +69,7 @@ def load():
         lib = ctypes.CDLL(_LIB_PATH)
         lib.gnn_workspace_bytes.restype = ctypes.c_size_t
         lib.gnn_backward_workspace_bytes.restype = ctypes.c_size_t
+        lib.gnn_model_workspace_bytes.restype = ctypes.c_size_t
         lib.gnn_strerror.restype = ctypes.c_char_p
         for name in _SYMBOLS:
             getattr(lib, name)  # AttributeError if the build lost a symbol
@@ -329,6 +330,47 @@ def gnn_layer_forward_timed(kind, n, nnz, rowptr, colidx, ew, eps, X, in_dim, W,
                                         _u32(flags), wp, wb, _stream(stream), _event(ev_agg_start),
                                         _event(ev_agg_stop))
     _check(rc, "gnn_layer_forward_timed")
+
+
+def gnn_model_workspace_bytes(n: int, nnz: int, dims: Sequence[int], ngs: int = 0) -> int:
+    d = (ctypes.c_int32 * len(dims))(*[int(x) for x in dims])
+    return int(load().gnn_model_workspace_bytes(_i32(n), _i64(nnz), _i32(len(dims) - 1), d, _i32(ngs)))
+
+
+class ModelCall:
+    """Arguments of gnn_model_forward marshalled once (pointer arrays, dims), for repeated calls on the
+    same tensors: model = ModelCall(...); model() enqueues one forward pass."""
+
+    def __init__(self, kind, n, nnz, rowptr, colidx, ew, eps, X, dims, Ws, bs, out, ngs=0, dw=0, waves_per_block=0,
+                 flags=0, workspace=None, stream=None, ev_agg_start=None, ev_agg_stop=None):
+        L = len(dims) - 1
+        if len(Ws) != L or (bs is not None and len(bs) != L):
+            raise ValueError("one weight matrix (and optionally one bias) per layer")
+        self._keep = (rowptr, colidx, ew, X, list(Ws), None if bs is None else list(bs), out, workspace)
+        ptr_array = ctypes.c_void_p * L
+        self._dims = (ctypes.c_int32 * (L + 1))(*[int(x) for x in dims])
+        self._W = ptr_array(*[_dev(W, "float32", "W").value for W in Ws])
+        self._b = None if bs is None else ptr_array(*[None if b is None else _dev(b, "float32", "b").value for b in bs])
+        ev = lambda evs: None if evs is None else ptr_array(*[None if e is None else _event(e).value for e in evs])
+        self._ev0, self._ev1 = ev(ev_agg_start), ev(ev_agg_stop)
+        wp, wb = _ws(workspace)
+        self._fn = load().gnn_model_forward
+        self._stream = stream
+        self._args = [ctypes.c_int(kind), _i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"),
+                      _dev(colidx, "int32", "colidx"), _dev(ew, "float32", "ew"), _f32(eps), _dev(X, "float32", "X"),
+                      _i32(L), self._dims, self._W, self._b, _dev(out, "float32", "out"), _i32(ngs), _i32(dw),
+                      _i32(waves_per_block), _u32(flags), wp, wb]
+
+    def __call__(self, flags=None):
+        args = self._args if flags is None else self._args[:16] + [_u32(flags)] + self._args[17:]
+        rc = self._fn(*args, _stream(self._stream), self._ev0, self._ev1)
+        _check(rc, "gnn_model_forward")
+
+
+def gnn_model_forward(kind, n, nnz, rowptr, colidx, ew, eps, X, dims, Ws, bs, out, ngs=0, dw=0, waves_per_block=0,
+                      flags=0, workspace=None, stream=None, ev_agg_start=None, ev_agg_stop=None):
+    ModelCall(kind, n, nnz, rowptr, colidx, ew, eps, X, dims, Ws, bs, out, ngs, dw, waves_per_block, flags, workspace,
+              stream, ev_agg_start, ev_agg_stop)()
 
 
 def gnn_backward_workspace_bytes(n: int, nnz: int, in_dim: int, out_dim: int, ngs: int = 0) -> int:

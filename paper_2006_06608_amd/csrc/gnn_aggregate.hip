@@ -110,8 +110,12 @@ __global__ __launch_bounds__(256) void k_agg_epilogue_spanning(AggParams p)
 #endif
 constexpr int kXcdRun = GNN_XCD_RUN;  // consecutive tiles that stay on one XCD
 
+// Register budget: the gather needs U*ITER*VEC registers for the rows in flight; the waves-per-SIMD
+// request keeps each variant at the occupancy its row buffer allows (8 waves: 64 registers, 7: 72,
+// 6: 80, 5: 96; the weighted and self-term variants carry a few more values) instead of landing one or two registers above a step.
 template <int VEC, int ITER, int U, bool WEIGHTED, bool SELF, int OP>
-__global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(ITER == 1 ? (WEIGHTED || SELF ? 7 : 8) : (ITER == 2 ? (WEIGHTED ? 6 : 7) : 5))))
+void k_aggregate(AggParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const WsHeader *hdr = p.hdr;

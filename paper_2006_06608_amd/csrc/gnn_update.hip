@@ -382,4 +382,58 @@ int gnn_layer_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, c
                                    waves_per_block, flags, workspace, workspace_bytes, stream, nullptr, nullptr);
 }
 
+// Layout of the model workspace: the layer workspace (partition, intermediate of the widest layer,
+// scratch of the ordered flush), then two activation buffers of n * (widest hidden layer) floats.
+static bool model_layout(int32_t n, int64_t nnz, int32_t num_layers, const int32_t *dims, int32_t ngs, size_t *layer_bytes,
+                         size_t *act_bytes)
+{
+    if (n < 0 || nnz < 0 || num_layers < 1 || !dims || ngs < 0) return false;
+    int32_t widest = 0, hidden = 0;
+    for (int32_t l = 0; l <= num_layers; ++l) {
+        if (dims[l] <= 0) return false;
+        if (dims[l] > widest) widest = dims[l];
+        if (l > 0 && l < num_layers && dims[l] > hidden) hidden = dims[l];
+    }
+    *layer_bytes = align_up(gnn_workspace_bytes(n, nnz, widest, ngs));
+    *act_bytes = align_up(sizeof(float) * (size_t)n * (size_t)hidden);
+    return true;
+}
+
+size_t gnn_model_workspace_bytes(int32_t n, int64_t nnz, int32_t num_layers, const int32_t *dims, int32_t ngs)
+{
+    size_t layer_bytes = 0, act_bytes = 0;
+    if (!model_layout(n, nnz, num_layers, dims, ngs, &layer_bytes, &act_bytes)) return 0;
+    return layer_bytes + 2 * act_bytes;
+}
+
+int gnn_model_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *ew,
+                      float eps, const float *X, int32_t num_layers, const int32_t *dims, const float *const *W,
+                      const float *const *b, float *out, int32_t ngs, int32_t dw, int32_t waves_per_block, uint32_t flags,
+                      void *workspace, size_t workspace_bytes, void *stream, void *const *ev_agg_start,
+                      void *const *ev_agg_stop)
+{
+    size_t layer_bytes = 0, act_bytes = 0;
+    if (!W || !model_layout(n, nnz, num_layers, dims, ngs, &layer_bytes, &act_bytes)) return GNN_EINVAL;
+    if (n == 0) return GNN_OK;
+    if (!workspace || ((uintptr_t)workspace) % kAlign != 0 || workspace_bytes < layer_bytes + 2 * act_bytes)
+        return GNN_EWORKSPACE;
+    // fix the group size once, so that the partition built by the first layer serves all of them
+    int32_t ngs_r = ngs, dw_r = 0, wpb_r = 0;
+    decide_defaults(n, nnz, 0, dims[0], 1, &ngs_r, &dw_r, &wpb_r);
+    float *act[2] = {(float *)((char *)workspace + layer_bytes), (float *)((char *)workspace + layer_bytes + act_bytes)};
+    const float *in = X;
+    for (int32_t l = 0; l < num_layers; ++l) {
+        const bool last = l == num_layers - 1;
+        float *dst = last ? out : act[l & 1];
+        const uint32_t f = l == 0 ? flags : (flags | GNN_FLAG_REUSE_PARTITION);
+        const int rc = gnn_layer_forward_timed(kind, n, nnz, rowptr, colidx, ew, eps, in, dims[l], W[l], b ? b[l] : nullptr,
+                                               dims[l + 1], last ? 0 : 1, dst, ngs_r, dw, waves_per_block, f, workspace,
+                                               layer_bytes, stream, ev_agg_start ? ev_agg_start[l] : nullptr,
+                                               ev_agg_stop ? ev_agg_stop[l] : nullptr);
+        if (rc != GNN_OK) return rc;
+        in = dst;
+    }
+    return GNN_OK;
+}
+
 }  // extern "C"

@@ -173,3 +173,44 @@ def test_config5_aggregation_for_every_group_size_of_the_sweep(ngs):
         _chains[key] = oracle.aggregate_gin(g.rowptr, g.colidx, 0.0, X, want_abs=True)
     ref, ab = _chains[key]
     assert_parity(run_gin(chain.G, 0.0, X, ngs=ngs), ref, ab, f"config 5 aggregation ngs {ngs}")
+
+
+# ------------------------------------------------------------------ whole model in one call
+@pytest.mark.parametrize("cfg,shrink", [(2, 4), (3, 8), (4, 32)])
+def test_model_forward_equals_the_layer_by_layer_chain_and_the_oracle(cfg, shrink):
+    from gnn_synth import config_spec
+    from util import parity_errors
+    from gpu_util import TOL, run_model
+    spec = config_spec(cfg)
+    g = config_graph(cfg, shrink=shrink)
+    dims = list(spec["dims"])
+    kind = gnn.GNN_GIN if spec["kind"] == "gin" else gnn.GNN_GCN
+    X = features(g.n, dims[0], seed=cfg)
+    Ws = [glorot(dims[i], dims[i + 1], seed=10 * cfg + i) for i in range(len(dims) - 1)]
+    bs = [features(1, dims[i + 1], seed=50 + i)[0] * 0.1 if i % 2 == 0 else None for i in range(len(dims) - 1)]
+    ew = oracle.gcn_norm(g.rowptr, g.colidx) if kind == gnn.GNN_GCN else None
+    G = DeviceGraph(g.rowptr, g.colidx, ew)
+    ws = torch.empty(gnn.gnn_model_workspace_bytes(G.n, G.nnz, dims, 0), dtype=torch.uint8, device="cuda")
+    out = torch.full((G.n, dims[-1]), float("nan"), device="cuda")
+    Wd = [dev(W) for W in Ws]
+    bd = [None if b is None else dev(b) for b in bs]
+    model = gnn.ModelCall(kind, G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), dims, Wd, bd, out, workspace=ws)
+    model()
+    torch.cuda.synchronize()
+    gnn.gnn_workspace_status(ws)
+    first = out.cpu().numpy().copy()
+    # same kernels in the same order as the chain of gnn_layer_forward calls: identical bits
+    chain = run_model(kind, G, 0.0, X, Ws, bs)
+    assert np.array_equal(first.view(np.uint32), chain.view(np.uint32))
+    ref = (oracle.gcn_model(g.rowptr, g.colidx, ew, X, Ws, bs) if kind == gnn.GNN_GCN
+           else oracle.gin_model(g.rowptr, g.colidx, 0.0, X, Ws, bs))
+    normwise, _ = parity_errors(first, ref, None)
+    assert normwise <= TOL, normwise
+    # a second call reusing the partition gives the same bits
+    out.fill_(float("nan"))
+    model(flags=gnn.GNN_FLAG_REUSE_PARTITION)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), first.view(np.uint32))
+    # too small a workspace is refused on the host
+    with pytest.raises(gnn.GnnError):
+        gnn.gnn_model_forward(kind, G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), dims, Wd, bd, out, workspace=ws[:4096])
