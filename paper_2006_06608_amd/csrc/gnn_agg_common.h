@@ -17,7 +17,7 @@ struct AggParams {
     const float *ew;
     const float *X;
     float *out;
-    float *det_part;    // ordered flush: float[2 * tiles * dim] partial rows of spanning nodes; else null
+    float *part_rows;    // ordered flush: float[2 * tiles * dim] partial rows of spanning nodes; else null
     int *cnt;           // ordered flush: per-node arrival counters (zero on entry and on exit)
     const float *bias;  // epilogue: out = act(sum + bias); may be null
     const int *rowptr;  // mean aggregation: a finished row is divided by its length; null otherwise

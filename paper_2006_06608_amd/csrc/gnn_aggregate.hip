@@ -121,7 +121,7 @@ void k_aggregate(AggParams p)
     const WsHeader *hdr = p.hdr;
     if (!header_ok(hdr, p)) {
         // with the ordered flush no kernel runs before this one: record why nothing was computed
-        if (p.det_part && blockIdx.x == 0 && threadIdx.x == 0) note_stale(p.hdr, p);
+        if (p.part_rows && blockIdx.x == 0 && threadIdx.x == 0) note_stale(p.hdr, p);
         return;
     }
 
@@ -288,7 +288,7 @@ void k_aggregate(AggParams p)
                         else store_vec<VEC>(p.out + (size_t)e.node * dim + d, r);
                     }
                 }
-            } else if (!p.det_part) {
+            } else if (!p.part_rows) {
                 // the node continues in another wave (or block): accumulate in its LDS slot
                 float *srow = s_slot + (size_t)slot * dim;
 #pragma unroll
@@ -302,8 +302,8 @@ void k_aggregate(AggParams p)
                 if (lastflag != 0 && tlane == 0) s_last[slot] = 1;
             }
         }
-        if (p.det_part) {
-            // deterministic mode: the waves add to the slots one after the other, in wave order (the
+        if (p.part_rows) {
+            // ordered flush: the waves add to the slots one after the other, in wave order (the
             // segment heads of one wave have distinct target nodes, so plain read-modify-writes do)
             const bool add = seg_head && !complete_in_wave;
             const int nw = blockDim.x >> 6;
@@ -333,7 +333,7 @@ void k_aggregate(AggParams p)
         float *orow = p.out + (size_t)e.node * dim;
         // ordered flush: the node of the block's first group goes to partial row 0 of the tile, any
         // other unfinished node (it can only be the node of the last group) to partial row 1
-        float *prow = p.det_part ? p.det_part + ((size_t)tile * 2 + (lay.team == 0 ? 0 : 1)) * dim : nullptr;
+        float *prow = p.part_rows ? p.part_rows + ((size_t)tile * 2 + (lay.team == 0 ? 0 : 1)) * dim : nullptr;
         for (int c = 0; c < p.iter_total; ++c) {
             const int d = (c * dwl + tlane) * VEC;
             if (d >= dim) break;
@@ -371,7 +371,7 @@ void k_aggregate(AggParams p)
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
                 if (tlane == 0) p.cnt[e.node] = 0;  // ready for the next call
                 // in its first tile the node is the tile's first node only if it starts the tile
-                const float *first_row = p.det_part + ((size_t)b0 * 2 + (gfirst % T == 0 ? 0 : 1)) * dim;
+                const float *first_row = p.part_rows + ((size_t)b0 * 2 + (gfirst % T == 0 ? 0 : 1)) * dim;
                 for (int c = 0; c < p.iter_total; ++c) {
                     const int d = (c * dwl + tlane) * VEC;
                     if (d >= dim) break;
@@ -383,7 +383,7 @@ void k_aggregate(AggParams p)
                         for (int q = 0; q < 4; ++q) {
 #pragma unroll
                             for (int j = 0; j < VEC; ++j) t[q][j] = op_identity<OP>();
-                            if (b + q <= b1) load_vec_coherent<VEC>(t[q], p.det_part + ((size_t)(b + q) * 2) * dim + d);
+                            if (b + q <= b1) load_vec_coherent<VEC>(t[q], p.part_rows + ((size_t)(b + q) * 2) * dim + d);
                         }
 #pragma unroll
                         for (int q = 0; q < 4; ++q)
@@ -482,7 +482,7 @@ static void launch_vec(int op, int iter, bool weighted, bool self, dim3 grid, di
 // Shared implementation of gnn_aggregate_gcn / gnn_aggregate_gin and of the aggregation step of
 // gnn_layer_forward.  self: add self_scale * X[i] (GIN).  bias/relu: fused epilogue.  ws_reserved:
 // bytes at the front of the workspace that the caller uses itself (0: only the partition); the
-// scratch of the deterministic mode is placed behind them.
+// partial rows of the ordered flush are placed behind them.
 int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr,
                           const int32_t *colidx, const float *ew, const float *X, float *out, int32_t dim, int32_t ngs,
                           int32_t dw, int32_t wpb, uint32_t flags, const float *bias, int relu, void *workspace,
@@ -530,7 +530,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     p.ew = ew;
     p.X = X;
     p.out = out;
-    p.det_part = nullptr;
+    p.part_rows = nullptr;
     p.cnt = (int *)(ws + L.cnt);
     p.bias = bias;
     p.rowptr = mean ? rowptr : nullptr;
@@ -568,9 +568,9 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
         return GNN_OK;
     }
 
-    // the workspace-size functions allow deterministic scratch for blocks of kDetMinTile groups
+    // the workspace-size functions allow deterministic scratch for blocks of kPartMinTile groups
     if ((det || !plain_sum) && auto_wpb)
-        while (wpb * (64 >> dwl_log2) < kDetMinTile && wpb < kMaxWavesPerBlock) wpb *= 2;
+        while (wpb * (64 >> dwl_log2) < kPartMinTile && wpb < kMaxWavesPerBlock) wpb *= 2;
     const int T = wpb * (64 >> dwl_log2);
     p.T = T;
     size_t lds = (size_t)(kMaxWavesPerBlock + T + (size_t)T * ngs * (weighted ? 2 : 1)) * 4;
@@ -586,13 +586,13 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     // Ordered flush (one launch, no float atomics, no zeroing pass) whenever the workspace has room
     // for the partial rows behind the caller's own use of it; the atomic flush of Sec. 5.2 otherwise
     // or on request.
-    float *det_part = nullptr;
+    float *part_rows = nullptr;
     {
         size_t off = L.total > ws_reserved ? L.total : ws_reserved;
         off = align_up(off);
-        if (off + det_scratch_bytes(ng_cap, T, dim) <= workspace_bytes) det_part = (float *)(ws + off);
+        if (off + part_rows_bytes(ng_cap, T, dim) <= workspace_bytes) part_rows = (float *)(ws + off);
     }
-    if ((det || !plain_sum) && !det_part) return GNN_EWORKSPACE;
+    if ((det || !plain_sum) && !part_rows) return GNN_EWORKSPACE;
 
     // GIN layer with the Update fused in (the caller falls back to separate kernels if not taken)
     if (fuse && (flags & GNN_FLAG_FUSION) && !det) {
@@ -611,7 +611,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     // persistent, pipelined kernel whenever its requirements hold
     const bool want_pipe =
         plain_sum && !det && !(flags & GNN_FLAG_NO_PIPELINE) && ((flags & GNN_FLAG_PIPELINE) || ngs <= 8);
-    const bool ordered = det || (det_part != nullptr && !atomic_flush);
+    const bool ordered = det || (part_rows != nullptr && !atomic_flush);
     const size_t plds = want_pipe ? pipe_lds_bytes(T, dim, ngs, dwl_log2, wpb, weighted) : 0;
     if (plds > 0 && plds <= kMaxLdsBytes) {
         int dev = 0, cus = 0;
@@ -646,7 +646,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     if (grid + extra >= ((int64_t)1 << 31)) return GNN_ELIMIT;
 
     // (the ordered flush adds nothing to `out`, so no row needs zeroing and no pass follows)
-    if (ordered) p.det_part = det_part;
+    if (ordered) p.part_rows = part_rows;
     else if (self) hipLaunchKernelGGL(k_agg_init<true>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
     else hipLaunchKernelGGL(k_agg_init<false>, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
 

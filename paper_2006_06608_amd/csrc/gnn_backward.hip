@@ -251,7 +251,7 @@ size_t gnn_backward_workspace_bytes(int32_t n, int64_t nnz, int32_t in_dim, int3
     // capacity for whatever group size the model may pick when ngs == 0 (ngs = 1 is the upper bound)
     const int32_t cap_ngs = ngs > 0 ? ngs : 1;
     return bwd_layout(n, nnz, in_dim, out_dim, cap_ngs).total +
-           det_scratch_bytes(ng_upper_bound(n, nnz, cap_ngs), kDetMinTile, in_dim > out_dim ? in_dim : out_dim);
+           part_rows_bytes(ng_upper_bound(n, nnz, cap_ngs), kPartMinTile, in_dim > out_dim ? in_dim : out_dim);
 }
 
 int gnn_layer_backward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr_t, const int32_t *colidx_t,

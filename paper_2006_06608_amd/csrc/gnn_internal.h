@@ -87,10 +87,10 @@ inline WsLayout ws_layout(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs_f
 // Ordered flush (the default when the workspace has room, required by GNN_FLAG_DETERMINISTIC): every
 // block may leave up to two partial rows (the node of its first and of its last neighbor group) in
 // scratch memory behind the caller's own use of the workspace.  The workspace-size functions allow
-// for blocks of at least kDetMinTile groups.
-constexpr int kDetMinTile = 16;
+// for blocks of at least kPartMinTile groups.
+constexpr int kPartMinTile = 16;
 
-inline size_t det_scratch_bytes(int64_t ng_capacity, int tile, int32_t dim)
+inline size_t part_rows_bytes(int64_t ng_capacity, int tile, int32_t dim)
 {
     if (dim <= 0) return 0;
     const int64_t tiles = (ng_capacity + tile - 1) / tile;

@@ -16,7 +16,7 @@ int partition_build_impl(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t 
 // gnn_aggregate.hip: shared implementation of gnn_aggregate_gcn / gnn_aggregate_gin and of the
 // aggregation step of the layer entry points.  self: add self_scale * X[i] (GIN).  bias/relu: fused
 // epilogue.  ws_reserved: bytes at the front of the workspace that the caller uses itself (0: only
-// the partition); the scratch of the deterministic mode is placed behind them.  ev_start/ev_stop
+// the partition); the partial rows of the ordered flush are placed behind them.  ev_start/ev_stop
 // (may be null) are recorded around the main kernel.  fuse (may be null): see FuseSpec.
 // op: kOpSum / kOpMax / kOpMin; mean: divide every finished row by its length (op must be kOpSum).
 // Anything but the plain sum takes no weights, no self term, and needs the ordered flush.

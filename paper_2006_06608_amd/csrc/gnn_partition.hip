@@ -255,7 +255,7 @@ size_t gnn_workspace_bytes(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs)
 {
     if (n < 0 || nnz < 0 || max_dim < 0 || ngs < 0) return 0;
     const WsLayout L = ws_layout(n, nnz, max_dim, ngs);
-    return L.total + det_scratch_bytes(L.ng_capacity, kDetMinTile, max_dim);
+    return L.total + part_rows_bytes(L.ng_capacity, kPartMinTile, max_dim);
 }
 
 int gnn_partition_build(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t ngs, void *workspace,
