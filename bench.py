@@ -267,7 +267,13 @@ def main():
 
     dom_bytes = algorithmic_bytes(dom_dim)
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
-    agg_dims = ([dims[0]] * layers if kind == "gin" else dims[1:]) if layers else [head_dim]
+    if not layers:
+        agg_dims = [head_dim]
+    elif kind == "gin":
+        agg_dims = [dims[0]] * layers
+    else:  # GCN aggregates at the output width, or at the input width of a widening layer on request
+        narrow = bool(args.flags & gnn.GNN_FLAG_GCN_NARROW_FIRST)
+        agg_dims = [dims[l] if narrow and dims[l] < dims[l + 1] else dims[l + 1] for l in range(layers)]
     edges_dim_step = float(nnz) * float(sum(agg_dims))
     value = edges_dim_step / (ms_per_step * 1e-3)
 

@@ -347,16 +347,28 @@ int gnn_layer_forward_timed(int kind, int32_t n, int64_t nnz, const int32_t *row
     if (n == 0) return GNN_OK;
     if (!X || !W || !out) return GNN_EINVAL;
     hipStream_t s = (hipStream_t)stream;
-    const int32_t agg_dim = kind == GNN_GCN ? out_dim : in_dim;
+    // GCN aggregates after the Update, at the layer's output width (Sec. 3.1: the Update reduces the
+    // dimension first).  For a layer that widens, A_hat (X W) = (A_hat X) W lets the aggregation run
+    // at the narrower input width instead; only on request, since it moves the rounding points.
+    const bool narrow_first = kind == GNN_GCN && (flags & GNN_FLAG_GCN_NARROW_FIRST) && in_dim < out_dim;
+    const int32_t agg_dim = (kind == GNN_GCN && !narrow_first) ? out_dim : in_dim;
     // the partition's capacity (and with it the offset of the intermediate) depends on ngs: resolve
     // the automatic choice here exactly as the aggregation will.  The intermediate sits at a
     // 256-byte aligned offset, so only the caller's pointer can narrow the vector width.
     int32_t ngs_r = ngs, dw_r = dw, wpb_r = waves_per_block;
-    decide_defaults(n, nnz, 0, agg_dim, pick_vec(agg_dim, kind == GNN_GCN ? (const void *)out : (const void *)X, nullptr),
+    decide_defaults(n, nnz, 0, agg_dim,
+                    pick_vec(agg_dim, (kind == GNN_GCN && !narrow_first) ? (const void *)out : (const void *)X, nullptr),
                     &ngs_r, &dw_r, &wpb_r);
     const WsLayout L = ws_layout(n, nnz, agg_dim, ngs_r);
     if (!workspace || ((uintptr_t)workspace) % kAlign != 0 || workspace_bytes < L.total) return GNN_EWORKSPACE;
     float *tmp = (float *)((char *)workspace + L.tmp);
+    flags &= ~GNN_FLAG_GCN_NARROW_FIRST;
+    if (narrow_first) {
+        int rc = aggregate_impl(false, 0.0f, n, nnz, rowptr, colidx, ew, X, tmp, in_dim, ngs_r, dw, waves_per_block, flags,
+                                nullptr, 0, workspace, workspace_bytes, L.total, s, ev0, ev1, nullptr);
+        if (rc != GNN_OK) return rc;
+        return update_gemm_impl(n, in_dim, out_dim, tmp, W, b, relu, out, s);
+    }
     if (kind == GNN_GCN) {
         // Update first (reduces the dimension), then Aggregation with the bias/activation fused
         int rc = update_gemm_impl(n, in_dim, out_dim, X, W, nullptr, 0, tmp, s);

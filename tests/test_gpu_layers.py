@@ -214,3 +214,35 @@ def test_model_forward_equals_the_layer_by_layer_chain_and_the_oracle(cfg, shrin
     # too small a workspace is refused on the host
     with pytest.raises(gnn.GnnError):
         gnn.gnn_model_forward(kind, G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), dims, Wd, bd, out, workspace=ws[:4096])
+
+
+def test_widening_gcn_layer_may_aggregate_first():
+    g = config_graph(4, shrink=16)
+    ew = oracle.gcn_norm(g.rowptr, g.colidx)
+    G = DeviceGraph(g.rowptr, g.colidx, ew)
+    X = features(g.n, 16, seed=91)
+    W = glorot(16, 22, seed=92)
+    b = features(1, 22, seed=93)[0] * 0.1
+    ref, scale = oracle.gcn_layer(g.rowptr, g.colidx, ew, X, W, b, True, want_abs=True)
+    ws = gnn.alloc_workspace(G.n, G.nnz, 22, 0)
+    outs = {}
+    for flags in (0, gnn.GNN_FLAG_GCN_NARROW_FIRST):
+        out = torch.full((G.n, 22), float("nan"), device="cuda")
+        gnn.gnn_layer_forward(gnn.GNN_GCN, G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), 16, dev(W), dev(b), 22, True,
+                              out, 0, 0, 0, flags, ws)
+        torch.cuda.synchronize()
+        gnn.gnn_workspace_status(ws)
+        outs[flags] = out.cpu().numpy()
+        # A_hat (X W) = (A_hat X) W: the same oracle value, the same error scale
+        assert_parity(outs[flags], ref, scale, f"gcn layer 16->22 flags {flags}")
+    # a narrowing layer ignores the flag: identical bits
+    W2 = glorot(22, 16, seed=94)
+    X2 = features(g.n, 22, seed=95)
+    res = []
+    for flags in (0, gnn.GNN_FLAG_GCN_NARROW_FIRST):
+        out = torch.full((G.n, 16), float("nan"), device="cuda")
+        gnn.gnn_layer_forward(gnn.GNN_GCN, G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X2), 22, dev(W2), None, 16, False,
+                              out, 0, 0, 0, flags, ws)
+        torch.cuda.synchronize()
+        res.append(out.cpu().numpy())
+    assert np.array_equal(res[0].view(np.uint32), res[1].view(np.uint32))
