@@ -33,7 +33,6 @@ MEASURED_TRAFFIC_BYTES = {
     (5, 32, True): 2.940e9,
     (4, 32, False): 0.476e9,  # k_aggregate<4,1,8,true,false>, Dim 16 (layer 1 of the 2-layer GCN)
     (4, 32, True): 0.286e9,
-    (3, 16, False): 0.036e9,  # k_aggregate<4,2,4,false,true>, Dim 64
 }
 
 
@@ -336,8 +335,13 @@ def main():
         cpu = {"value": float(nnz) * sum(done_dims) / dt, "unit": "edge*dim/s", "cores": 1, "kind": "oracle",
                "sample": f"{sample} ({dt:.1f} s)"}
 
-    # the pipelined kernel is chosen for small groups when every resident block gets several tiles
+    # the pipelined kernel is chosen for small groups when every resident block gets several tiles; a GIN
+    # layer on a graph with short rows (or on request) runs as one fused kernel, aggregation + Update
     kname = "k_aggregate" if (ngs > 8 and not args.flags & 16) or args.flags & 8 else "k_aggregate_pipe|k_aggregate"
+    fused = (kind == "gin" and layers > 0 and not args.flags & (128 | 512) and
+             (args.flags & 64 or (nnz / max(n, 1) < 8 and not args.flags & (4 | 8 | 16))))
+    if fused:
+        kname = "k_gin_layer_fused (aggregation + Update GEMM in one kernel)"
     rec = {
         "metric": "aggregation edges*dim/s over one model forward (aggregations + Update GEMMs)",
         "value": value,
@@ -358,7 +362,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": f"{kname} ({kind.upper()}, Dim {dom_dim})", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": (MEASURED_TRAFFIC_BYTES.get((cfg, ngs, bool(args.renumber)))
-                                 if args.replicate == 1 and not args.hidden and not args.flags else None),
+                                 if args.replicate == 1 and not args.hidden and not args.flags and not fused else None),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_kernel_ms": dom_ms},
         "cpu_baseline": cpu,
         "aggregation_kernel_ms_per_layer": [float(x) for x in agg_ms_layers],

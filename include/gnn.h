@@ -75,11 +75,14 @@ extern "C" {
                                        without room is an error (GNN_EWORKSPACE) and the general kernel is
                                        always used.  Not combinable with GNN_FLAG_NO_BLOCK_OPT or
                                        GNN_FLAG_ATOMIC_FLUSH (GNN_EINVAL) */
-#define GNN_FLAG_FUSION 64u         /* gnn_layer_forward(GNN_GIN): fuse the Update GEMM into the aggregation
-                                       kernel where the shape allows (in_dim <= 128 and a multiple of 4,
-                                       out_dim <= 64, <= 4 waves per block).  Opt-in: on the R-MAT
-                                       configuration it is slower than the two separate kernels */
-
+#define GNN_FLAG_FUSION 64u         /* gnn_layer_forward / gnn_model_forward, GNN_GIN: fuse the Update GEMM into
+                                       the aggregation kernel where the shape allows (in_dim <= 128 and a
+                                       multiple of 4, out_dim <= 64, <= 8 waves per block, a multiple of
+                                       ceil(out_dim/16), workspace with room for the ordered flush).  The
+                                       library fuses by itself when the mean row has fewer than 8 entries
+                                       (batches of small graphs: one launch per layer, -20 %); on graphs with
+                                       long rows the two separate kernels are faster, hence the flag */
+#define GNN_FLAG_NO_FUSION 512u     /* never fuse */
 #define GNN_FLAG_ATOMIC_FLUSH 128u  /* always finish nodes that span blocks the way Sec. 5.2 describes: the
                                        leader adds the block's partial row to global memory with one float
                                        atomic per element (rows zeroed by a kernel that runs first, bias and

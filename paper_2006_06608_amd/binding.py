@@ -10,7 +10,7 @@ import numpy as np
 __all__ = [
     "GnnError", "lib_path", "load", "exported_symbols",
     "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_XCD_RUNS", "GNN_FLAG_NO_PIPELINE",
-    "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
+    "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_FLAG_NO_FUSION", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
     "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
@@ -26,6 +26,7 @@ GNN_FLAG_DETERMINISTIC = 32
 GNN_FLAG_FUSION = 64
 GNN_FLAG_ATOMIC_FLUSH = 128
 GNN_FLAG_GCN_NARROW_FIRST = 256
+GNN_FLAG_NO_FUSION = 512
 GNN_REDUCE_SUM, GNN_REDUCE_MAX, GNN_REDUCE_MIN, GNN_REDUCE_MEAN = 0, 1, 2, 3
 
 _PKG = os.path.dirname(os.path.abspath(__file__))

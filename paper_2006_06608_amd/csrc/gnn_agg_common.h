@@ -150,6 +150,22 @@ __device__ __forceinline__ bool header_ok(const WsHeader *hdr, const AggParams &
     return (magic == kMagic) & (status == GNN_OK) & (ngs == p.ngs) & (n == p.n) & (nnz == p.nnz);
 }
 
+// The workspace does not hold the partition the launch was prepared for: record why nothing was
+// computed (one thread).
+__device__ __forceinline__ void note_stale(WsHeader *hdr, const AggParams &p)
+{
+    if (hdr->magic != kMagic) {
+        hdr->magic = kMagic;
+        hdr->n = p.n;
+        hdr->nnz = p.nnz;
+        hdr->ngs = 0;
+        hdr->num_ng = 0;
+        hdr->status = GNN_ESTALE;
+    } else if (hdr->status == GNN_OK) {
+        hdr->status = GNN_ESTALE;
+    }
+}
+
 // 1 / (row length) for the mean aggregation, 1 otherwise.
 __device__ __forceinline__ float row_scale(const AggParams &p, int node)
 {

@@ -30,22 +30,6 @@
 
 namespace gnn {
 
-// The workspace does not hold the partition the launch was prepared for: record why nothing was
-// computed (one thread).
-__device__ inline void note_stale(WsHeader *hdr, const AggParams &p)
-{
-    if (hdr->magic != kMagic) {
-        hdr->magic = kMagic;
-        hdr->n = p.n;
-        hdr->nnz = p.nnz;
-        hdr->ngs = 0;
-        hdr->num_ng = 0;
-        hdr->status = GNN_ESTALE;
-    } else if (hdr->status == GNN_OK) {
-        hdr->status = GNN_ESTALE;
-    }
-}
-
 // Rows the main kernel will not store plainly: rows without entries get their final value, rows
 // whose groups span several blocks are zeroed for the atomic adds.  One wave scans 64 nodes.
 template <bool SELF>
@@ -568,6 +552,38 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
         return GNN_OK;
     }
 
+    // GIN layer with the Update fused in: on request, and by itself for graphs with short rows, where
+    // it measured faster than the two separate kernels (one launch per layer, the aggregate never
+    // goes to memory).  The caller runs the Update separately if the shape is not covered.
+    if (fuse) fuse->done = false;
+    const double avg_row = n > 0 ? (double)nnz / (double)n : 0.0;
+    const bool kernel_chosen = (flags & (GNN_FLAG_PIPELINE | GNN_FLAG_NO_PIPELINE | GNN_FLAG_XCD_RUNS)) != 0;
+    if (fuse && !atomic_flush && !(flags & GNN_FLAG_NO_FUSION) &&
+        ((flags & GNN_FLAG_FUSION) || (avg_row < 8.0 && !kernel_chosen))) {
+        const int wpb_f = auto_wpb ? 8 : wpb;  // large tiles amortise the copy of W every block makes
+        AggParams pf = p;
+        pf.T = wpb_f * (64 >> dwl_log2);
+        const int32_t part_dim = fuse->M > dim ? fuse->M : dim;  // fused partial rows are M wide
+        size_t off = L.total > ws_reserved ? L.total : ws_reserved;
+        off = align_up(off);
+        if (off + part_rows_bytes(ng_cap, pf.T, part_dim) <= workspace_bytes) {
+            pf.part_rows = (float *)(ws + off);
+            if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
+            const int rc = try_gin_layer_fused(pf, vec, wpb_f, fuse->W, fuse->b, fuse->out, fuse->M, fuse->relu,
+                                                (ng_cap + pf.T - 1) / pf.T, s);
+            if (rc < 0) return rc;
+            if (rc == GNN_OK) {
+                if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
+                fuse->done = true;
+                GNN_HIP_TRY(hipGetLastError());
+                return GNN_OK;
+            }
+            // not covered: the taps are recorded again around the aggregation kernel below
+        } else if (det) {
+            return GNN_EWORKSPACE;
+        }
+    }
+
     // the workspace-size functions allow deterministic scratch for blocks of kPartMinTile groups
     if ((det || !plain_sum) && auto_wpb)
         while (wpb * (64 >> dwl_log2) < kPartMinTile && wpb < kMaxWavesPerBlock) wpb *= 2;
@@ -593,20 +609,6 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
         if (off + part_rows_bytes(ng_cap, T, dim) <= workspace_bytes) part_rows = (float *)(ws + off);
     }
     if ((det || !plain_sum) && !part_rows) return GNN_EWORKSPACE;
-
-    // GIN layer with the Update fused in (the caller falls back to separate kernels if not taken)
-    if (fuse && (flags & GNN_FLAG_FUSION) && !det) {
-        fuse->done = false;
-        if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
-        const int rc = try_gin_layer_fused(p, vec, wpb, fuse->W, fuse->b, fuse->out, fuse->M, fuse->relu, tiles_upper,
-                                           (flags & GNN_FLAG_FUSION) != 0, s);
-        if (rc < 0) return rc;
-        if (rc == GNN_OK) {
-            if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
-            fuse->done = true;
-            return GNN_OK;
-        }
-    }
 
     // persistent, pipelined kernel whenever its requirements hold
     const bool want_pipe =

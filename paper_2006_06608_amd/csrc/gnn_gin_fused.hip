@@ -1,217 +1,233 @@
-// GIN layer with the Update fused into the Aggregation (an MI355X addition; the paper runs the two
-// phases as separate kernels): out = act(((1+eps) X + sum_N X) W + b) in one pass.
+// GIN layer with the Update fused into the Aggregation, built on the general aggregation kernel:
+// out = act(((1+eps) X + sum_N X) W + b) in one launch (an MI355X addition; the paper runs the two
+// phases as separate kernels).
 //
-// The persistent, software-pipelined aggregation (see gnn_aggregate_pipe.hip) leaves every target
-// node of a tile as one row of an LDS tile A[T][K] (Algorithm 1 slots, now used for all nodes).
-// After the tile's single barrier the block multiplies A by W with v_mfma_f32_16x16x4_f32 -- each
-// wave owns 16 output columns whose W fragments stay in registers for the whole kernel -- and
-// writes act(. + b) for nodes complete in the tile.  A node that spans tiles contributes
-// (partial row) W with global atomic adds, which is valid because the product is linear; its bias
-// and activation are applied by the follow-up kernel that already serves such rows.  The
-// aggregated matrix never goes to HBM and the separate GEMM kernel disappears.
-//
-// Opt-in (GNN_FLAG_FUSION).  Measured on the R-MAT configuration (1,048,576 nodes, Dim 64 -> 64) the
-// fused layer takes 690 us against 597 us for aggregation + GEMM run separately: all rows pass
-// through LDS, the register budget of the W fragments lowers occupancy to 4 waves per SIMD, the MFMA
-// phase sits on every tile's critical path, and the 48 % of rows without neighbours need the
-// product anyway.  It is kept for shapes where the aggregated matrix dominates the traffic.
-//
-// LDS slots are triple-buffered: the buffer read by the MFMA phase of tile i is cleared after the
-// barrier of tile i+1 and refilled during tile i+3, so one barrier per tile still suffices.
+// A block aggregates its neighbor groups exactly as k_aggregate does, but every target node of the
+// block ends up as one row of an LDS tile A[T][K] (the Algorithm 1 slots, the waves adding in wave
+// order).  After the barrier the block multiplies the tile by W, which it staged in LDS at its start,
+// with v_mfma_f32_16x16x4_f32: wave w owns the 16 output columns w mod ct of the row tiles
+// w / ct, w / ct + W/ct, ...  A node complete in the block gets act(row W + b) stored.  For a node
+// that spans blocks the product is applied to the block's partial row, which is valid because the
+// product is linear: (sum of partial rows) W = sum of (partial row W); the transformed partial row
+// (out_dim floats) then takes the ordered flush: device-coherent store, arrival counter, the block
+// that arrives last adds the partial rows in block order and applies bias and activation.  Rows
+// without any entry, act((1+eps) x W + b), are served by blocks appended to the grid whose waves
+// compact 16 such rows at a time and feed them to the same MFMA path straight from global memory.
+// The aggregated matrix never goes to HBM and the separate GEMM kernel disappears.
 #include <hip/hip_runtime.h>
 
 #include "gnn_launch.h"
-#include "gnn_pipe_common.h"
 
 namespace gnn {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 struct FusedParams {
-    AggParams a;     // X = layer input [n,K], dim = K, self_scale = 1 + eps; out/bias/relu unused
+    AggParams a;     // X = layer input [n,K], dim = K, self_scale = 1 + eps, part_rows [2*tiles][M], cnt
     const float *W;  // [K,M]
     const float *b;  // [M] or null
     float *out;      // [n,M]
     int M;
     int relu;
-    int ct;          // 16-column tiles of the output
+    int ct;          // 16-column tiles of the output (1..4)
+    int a_rows;      // rows of the LDS tile: T rounded up to whole 16-row MFMA tiles
 };
 
-// C[16 x 16] = A_tile[16 x 16*NS] . W fragment, for one row tile.
-template <int NS>
-__device__ __forceinline__ f32x4 tile_mfma(const float *arow, const float (&wreg)[4 * NS], int lk)
+__device__ __forceinline__ float act_bias(float v, float bcol, int relu)
 {
-    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        const float4 a4 = *reinterpret_cast<const float4 *>(arow + 16 * s + 4 * lk);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, wreg[4 * s + 0], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, wreg[4 * s + 1], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, wreg[4 * s + 2], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, wreg[4 * s + 3], acc, 0, 0, 0);
-    }
-    return acc;
+    v += bcol;
+    return relu ? fmaxf(v, 0.0f) : v;
 }
 
 template <int ITER, int U, int NS>
-__global__ __launch_bounds__(256) void k_gin_layer_fused(FusedParams fp)
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(ITER == 1 ? 6 : 5)))
+void k_gin_layer_fused(FusedParams fp)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const AggParams &p = fp.a;
     const WsHeader *hdr = p.hdr;
-    if (!header_ok(hdr, p)) return;
-
+    if (!header_ok(hdr, p)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) note_stale(p.hdr, p);
+        return;
+    }
     constexpr int VEC = 4;
-    constexpr int KP = 16 * NS;   // K padded to the MFMA step group
-    constexpr int LDA = KP + 4;   // row stride of the LDS tile (bank spread for the 16-byte reads)
-    const int T = p.T, dim = p.dim, ngs = p.ngs, M = fp.M;
-    const int64_t num_ng = hdr->num_ng;
-    const int64_t tiles = (num_ng + T - 1) / T;
+    constexpr int KP = 16 * NS;  // K padded to whole MFMA step groups
+    constexpr int LDA = KP + 4;  // row stride of the LDS tile
+    const int T = p.T, dim = p.dim, M = fp.M, ct = fp.ct;
+    const int LDW = 16 * ct + 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nwaves = blockDim.x >> 6;
+    const int nw = blockDim.x >> 6;
     const int dwl_log2 = p.dwl_log2, dwl = 1 << dwl_log2;
-    const int G = 64 >> dwl_log2;
     const int tlane = lane & (dwl - 1);
     const int team_in_wave = lane >> dwl_log2;
-    const int wcap = G * ngs;
     const int lrow = lane & 15, lk = lane >> 4;
 
-    // LDS: [3][T][LDA] tile | [3][T] node of slot | [3][T] flags of slot | [2][nwaves][wcap] indices | [64] list
-    float *s_A = reinterpret_cast<float *>(smem);
-    int *s_node = reinterpret_cast<int *>(s_A + 3 * (size_t)T * LDA);
-    int *s_flag = s_node + 3 * T;
-    int *s_col = s_flag + 3 * T;
-    int *s_list = s_col + 2 * (size_t)nwaves * wcap;
+    // LDS: wave counts [16] | s_last [T] | s_node [T] | s_state [T] | s_col [T*ngs] | (16-byte aligned)
+    //      s_W [KP][LDW] | s_A [a_rows][LDA] | per-wave lists [nw][64]
+    int *s_wave_cnt = reinterpret_cast<int *>(smem);
+    int *s_last = s_wave_cnt + kMaxWavesPerBlock;
+    int *s_node = s_last + T;
+    int *s_state = s_node + T;
+    int *s_col = s_state + T;
+    size_t off_w = (size_t)(kMaxWavesPerBlock + 3 * T + (size_t)T * p.ngs) * 4;
+    off_w = (off_w + 15) & ~(size_t)15;
+    float *s_W = reinterpret_cast<float *>(smem + off_w);
+    float *s_A = s_W + (size_t)KP * LDW;
+    int *s_list = reinterpret_cast<int *>(s_A + (size_t)fp.a_rows * LDA);
 
-    for (int i = tid; i < 3 * T * LDA; i += blockDim.x) s_A[i] = 0.0f;
-    for (int i = tid; i < 3 * T; i += blockDim.x) s_flag[i] = 0;
+    // One tile per block (several per block measured slower: they run one after the other, and the
+    // loop costs registers).  Surplus blocks of the over-sized grid leave before they touch anything.
+    const bool tile_block = (int64_t)blockIdx.x < p.tile_blocks;
+    const int64_t num_ng = hdr->num_ng;
+    const int64_t tiles = (num_ng + T - 1) / T;
+    const int64_t tile = blockIdx.x;
+    if (tile_block && tile >= tiles) return;
 
-    // this wave's output columns and its W fragments: wreg[4s+q] = W[16s + 4*lk + q][16*ct_w + lrow]
-    const int ct_w = wave % fp.ct;
-    const int rt_first = wave / fp.ct, rt_step = nwaves / fp.ct;  // row tiles handled by this wave
-    const int col = 16 * ct_w + lrow;
-    float wreg[4 * NS];
-#pragma unroll
-    for (int j = 0; j < 4 * NS; ++j) {
-        const int k = 16 * (j >> 2) + 4 * lk + (j & 3);
-        wreg[j] = (k < dim && col < M) ? fp.W[(size_t)k * M + col] : 0.0f;
+    // W into LDS (zero padded to KP rows and 64 columns): thread t takes the float4 (t mod 16) of the
+    // rows t/16, t/16 + blockDim/16, ...; the loads overlap with what follows
+    {
+        const int c = (tid & 15) * 4;
+        const bool vecw = (M % 4 == 0) && (((uintptr_t)fp.W & 15) == 0);
+        for (int k = tid >> 4; k < KP; k += blockDim.x >> 4) {
+            float4 w4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < dim && c < M) {
+                const float *src = fp.W + (size_t)k * M + c;
+                if (vecw) {
+                    w4 = *reinterpret_cast<const float4 *>(src);
+                } else {
+                    w4.x = src[0];
+                    if (c + 1 < M) w4.y = src[1];
+                    if (c + 2 < M) w4.z = src[2];
+                    if (c + 3 < M) w4.w = src[3];
+                }
+            }
+            if (c < 16 * ct) *reinterpret_cast<float4 *>(s_W + k * LDW + c) = w4;
+        }
     }
+
+    // this wave's output columns
+    const int ct_w = wave % ct;
+    const int rt_first = wave / ct, rt_step = nw / ct;
+    const int col = 16 * ct_w + lrow;
     const float bcol = (fp.b && col < M) ? fp.b[col] : 0.0f;
-    __syncthreads();
+    const float *wcol = s_W + 16 * ct_w + lrow;  // + k * LDW
 
-    const int64_t B = gridDim.x, b = blockIdx.x;
-    const bool remap = p.xcd_remap && (B % kNumXcd == 0);
-    const int64_t J = B / kNumXcd, xj = b / kNumXcd, xx = b % kNumXcd;
-    auto tile_of = [&](int64_t i) -> int64_t { return remap ? (i * kNumXcd + xx) * J + xj : i * B + b; };
-    auto fetch_tuples = [&](int64_t tile) -> NgEntry {
-        NgEntry e;
-        e.node = -1;
-        e.start = e.end = e.flags = 0;
-        if (tile < tiles) {
-            const int64_t g = tile * T + lane;
-            if (lane < T && g < num_ng) e = p.ng[g];
-        }
-        return e;
-    };
-    int cpre[kPipeIdxLoads];
-    auto prefetch_idx = [&](const TileView &V) {
+    if (!tile_block) {
+        // ---- rows without entries: act((1+eps) x W + b); every wave works alone
+        __syncthreads();  // W is in LDS
+        int *mylist = s_list + wave * 64;
+        const int64_t nchunks = ((int64_t)p.n + 63) / 64;
+        const int64_t first_chunk = ((int64_t)blockIdx.x - p.tile_blocks) * nw + wave;
+        const int64_t chunk_stride = (int64_t)p.extra_blocks * nw;
+        for (int64_t c = first_chunk; c < nchunks; c += chunk_stride) {
+            const int64_t v = c * 64 + lane;
+            const bool empty = v < p.n && p.ngptr[v] == p.ngptr[v + 1];
+            const unsigned long long m = __ballot(empty);
+            if (m == 0ull) continue;
+            const int cnt = __popcll(m);
+            if (empty) mylist[__popcll(m & ((1ull << lane) - 1ull))] = lane;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            for (int base = 0; base < cnt; base += 16) {
+                // lane (lrow, lk) feeds row `lrow` of this group of 16 rows, k = 16s + 4*lk .. +3
+                const bool rok = base + lrow < cnt;
+                const int64_t node = c * 64 + (rok ? mylist[base + lrow] : 0);
+                float4 a4[NS];
 #pragma unroll
-        for (int r = 0; r < kPipeIdxLoads; ++r) {
-            const int k = lane + 64 * r;
-            cpre[r] = 0;
-            if (k < V.ws1 - V.ws0) cpre[r] = load_stream(&p.colidx[V.ws0 + k]);
-        }
-    };
-    auto commit_idx = [&](const TileView &V, int buf) {
-        int *dc = s_col + ((size_t)buf * nwaves + wave) * wcap;
+                for (int s = 0; s < NS; ++s) {
+                    const int k = 16 * s + 4 * lk;
+                    a4[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (rok && k < dim) a4[s] = *reinterpret_cast<const float4 *>(p.X + (size_t)node * dim + k);
+                }
+                for (int t = 0; t < ct; ++t) {
+                    const float *wc = s_W + 16 * t + lrow;
+                    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int r = 0; r < kPipeIdxLoads; ++r) {
-            const int k = lane + 64 * r;
-            if (k < V.ws1 - V.ws0) dc[k] = cpre[r];
-        }
-    };
-
-    // Multiply the rows [0, nrows) of tile buffer `sb` by W and write them; every wave takes part.
-    auto multiply_and_store = [&](int sb, int nrows) {
-        const float *At = s_A + (size_t)sb * T * LDA;
-        const int *nodes = s_node + sb * T, *flags = s_flag + sb * T;
-        for (int rt = rt_first; rt * 16 < nrows; rt += rt_step) {
-            const f32x4 acc = tile_mfma<NS>(At + (size_t)(16 * rt + lrow) * LDA, wreg, lk);
-            if (col < M) {
+                    for (int s = 0; s < NS; ++s) {
+                        const int k = 16 * s + 4 * lk;
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[s].x, wc[(k + 0) * LDW], acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[s].y, wc[(k + 1) * LDW], acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[s].z, wc[(k + 2) * LDW], acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[s].w, wc[(k + 3) * LDW], acc, 0, 0, 0);
+                    }
+                    const int cc = 16 * t + lrow;
+                    const float bc = (fp.b && cc < M) ? fp.b[cc] : 0.0f;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int r = 16 * rt + 4 * lk + i;  // MFMA result row -> slot
-                    if (r < nrows) {
-                        const int node = nodes[r];
-                        float *o = fp.out + (size_t)node * M + col;
-                        if ((flags[r] & 3) == 3) {
-                            float v = acc[i] + bcol;
-                            if (fp.relu) v = fmaxf(v, 0.0f);
-                            *o = v;
-                        } else {
-                            atomicAdd(o, acc[i]);
+                    for (int i = 0; i < 4; ++i) {
+                        const int r = base + 4 * lk + i;  // result row -> position in the list
+                        if (r < cnt && cc < M) {
+                            const int64_t nd = c * 64 + mylist[r];
+                            fp.out[(size_t)nd * M + cc] = act_bias(p.self_scale * acc[i], bc, fp.relu);
                         }
                     }
                 }
             }
+            __builtin_amdgcn_wave_barrier();
         }
-    };
-    // Clear tile buffer `sb` (rows [0, nrows)) for its next use; every thread takes part.
-    auto clear_tile = [&](int sb, int nrows) {
-        float *At = s_A + (size_t)sb * T * LDA;
-        for (int i = tid; i < nrows * LDA; i += blockDim.x) At[i] = 0.0f;
-        for (int i = tid; i < nrows; i += blockDim.x) s_flag[sb * T + i] = 0;
-    };
+        return;
+    }
 
-    NgEntry tl_next = fetch_tuples(tile_of(1));
-    TileView cur = derive_tile(fetch_tuples(tile_of(0)), dwl_log2, T);
-    prefetch_idx(cur);
-    commit_idx(cur, 0);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    int *s_shared = s_wave_cnt + kMaxWavesPerBlock - 1;  // 1: some node of the tile is shared by several waves
+    {
+        const int64_t g0 = tile * T;
+        const BlockLayout lay = block_layout(p.ng, g0, num_ng, dwl_log2, s_wave_cnt);
+        const NgEntry e = lay.e;
 
-    int prev_rows = 0;  // slots used by the previous tile (to be cleared after this tile's barrier)
-    int64_t it = 0;
-    for (;; ++it) {
-        if (tile_of(it) >= tiles) break;
-        const int buf = (int)(it & 1), sb = (int)(it % 3), sb_prev = (int)((it + 2) % 3);
-        const NgEntry tl_after = fetch_tuples(tile_of(it + 2));
-        const TileView nxt = derive_tile(tl_next, dwl_log2, T);
-        prefetch_idx(nxt);
+        // stage the tile's contiguous CSR range, clear the LDS tile
+        const int64_t g_last = (g0 + T < num_ng ? g0 + T : num_ng) - 1;
+        const int e0 = p.ng[g0].start;
+        const int e1 = p.ng[g_last].end;
+        for (int i = tid; i < e1 - e0; i += blockDim.x) s_col[i] = load_stream(&p.colidx[e0 + i]);
+        for (int i = tid; i < T * LDA; i += blockDim.x) s_A[i] = 0.0f;
+        for (int i = tid; i < T; i += blockDim.x) {
+            s_last[i] = 0;
+            s_state[i] = 0;
+        }
+        if (tid == 0) *s_shared = 0;
+        __syncthreads();  // (this also publishes W)
+        const int slot = block_layout_slot(lay, dwl_log2, s_wave_cnt);
+        int nslots = 0;
+        for (int w = 0; w < nw; ++w) nslots += s_wave_cnt[w];
 
-        const NgEntry e = cur.e;
-        const int len = cur.valid ? e.end - e.start : 0;
-        const int off = e.start - cur.ws0;
+        const int len = lay.valid ? e.end - e.start : 0;
+        const int off = lay.valid ? e.start - e0 : 0;
         const bool first = (e.flags & 1) != 0;
-        const int *lc = s_col + ((size_t)buf * nwaves + wave) * wcap + off;
-        float *At = s_A + (size_t)sb * T * LDA;
-
-        const unsigned long long cont = __ballot(cur.valid && !cur.leader && team_in_wave > 0);
-        const bool seg_head = cur.valid && (team_in_wave == 0 || cur.leader);
-        int lastflag = cur.valid ? (e.flags & 2) : 0;
+        const unsigned long long cont = __ballot(lay.valid && !lay.leader && team_in_wave > 0);
+        const bool seg_head = lay.valid && (team_in_wave == 0 || lay.leader);
+        int lastflag = lay.valid ? (e.flags & 2) : 0;
         bool lastflag_done = false;
 
         for (int c0 = 0; c0 < p.iter_total; c0 += ITER) {
             float acc[ITER][VEC];
             bool dok[ITER];
+            const float *xb = p.X + (size_t)(c0 * dwl + tlane) * VEC;
 #pragma unroll
             for (int c = 0; c < ITER; ++c) {
                 dok[c] = ((c0 + c) * dwl + tlane) * VEC < dim;
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) acc[c][j] = 0.0f;
+                if (first && len > 0 && dok[c]) {  // the node's own row, as one more term of its first group
+                    float xs[VEC];
+                    load_vec<VEC>(xs, xb + (size_t)e.node * dim + (size_t)c * dwl * VEC);
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) acc[c][j] = p.self_scale * xs[j];
+                }
             }
-            const float *xb = p.X + (size_t)(c0 * dwl + tlane) * VEC;
             for (int base = 0; base < len; base += U) {
                 int colv[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) colv[u] = (base + u < len) ? lc[base + u] : -1;
+                for (int u = 0; u < U; ++u) {
+                    const int cu = s_col[off + base + u];
+                    colv[u] = base + u < len ? cu : -1;
+                }
                 float v[U][ITER][VEC];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
 #pragma unroll
                     for (int c = 0; c < ITER; ++c) {
                         if (colv[u] >= 0 && dok[c]) {
-                            load_vec<VEC>(v[u][c], xb + (size_t)colv[u] * dim + (size_t)c * dwl * VEC);
+                            load_vec<VEC>(v[u][c],
+                                          xb + (size_t)(unsigned)colv[u] * (unsigned)dim + (size_t)c * dwl * VEC);
                         } else {
 #pragma unroll
                             for (int j = 0; j < VEC; ++j) v[u][c][j] = 0.0f;
@@ -226,7 +242,7 @@ __global__ __launch_bounds__(256) void k_gin_layer_fused(FusedParams fp)
                         for (int j = 0; j < VEC; ++j) acc[c][j] += v[u][c][j];
             }
             if (cont != 0ull) {
-                const int key = cur.valid ? e.node : -1;
+                const int key = lay.valid ? e.node : -1;
                 for (int o = dwl; o < 64; o <<= 1) {
                     const int okey = __shfl_down(key, o);
                     const bool take = (lane + o < 64) && key >= 0 && okey == key;
@@ -244,84 +260,127 @@ __global__ __launch_bounds__(256) void k_gin_layer_fused(FusedParams fp)
                 }
             }
             lastflag_done = true;
+            // A node whose groups all sit in this wave owns its row of the tile: plain store.  Rows
+            // shared by several waves are added wave after wave (the segment heads of one wave have
+            // distinct target nodes), only in tiles that have such rows.
+            const bool own_row = seg_head && first && lastflag != 0;
             if (seg_head) {
-                float *srow = At + (size_t)cur.slot * LDA;
+                if (own_row) {
+                    float *srow = s_A + (size_t)slot * LDA;
 #pragma unroll
-                for (int c = 0; c < ITER; ++c) {
-                    const int d = ((c0 + c) * dwl + tlane) * VEC;
-                    if (d < dim) {
-                        if (first) {  // the team holding the node's first group also brings the self term
-                            float xs[VEC];
-                            load_vec<VEC>(xs, p.X + (size_t)e.node * dim + d);
+                    for (int c = 0; c < ITER; ++c) {
+                        const int d = ((c0 + c) * dwl + tlane) * VEC;
+                        if (d < dim)
+                            *reinterpret_cast<float4 *>(srow + d) = make_float4(acc[c][0], acc[c][1], acc[c][2], acc[c][3]);
+                    }
+                    if (tlane == 0) s_last[slot] = 1;
+                } else if (tlane == 0) {
+                    *s_shared = 1;
+                }
+            }
+            __syncthreads();
+            if (*s_shared != 0) {
+                for (int w = 0; w < nw; ++w) {
+                    if (wave == w && seg_head && !own_row) {
+                        float *srow = s_A + (size_t)slot * LDA;
 #pragma unroll
-                            for (int j = 0; j < VEC; ++j) acc[c][j] = fmaf(p.self_scale, xs[j], acc[c][j]);
+                        for (int c = 0; c < ITER; ++c) {
+                            const int d = ((c0 + c) * dwl + tlane) * VEC;
+                            if (d < dim) {
+                                float4 cur = *reinterpret_cast<float4 *>(srow + d);
+                                cur.x += acc[c][0];
+                                cur.y += acc[c][1];
+                                cur.z += acc[c][2];
+                                cur.w += acc[c][3];
+                                *reinterpret_cast<float4 *>(srow + d) = cur;
+                            }
                         }
+                        if (lastflag != 0 && tlane == 0) s_last[slot] = 1;
+                    }
+                    __syncthreads();
+                }
+            }
+        }
+
+        // what happens to each slot: 1 = complete in this tile, 2 / 3 = partial row 0 / 1 of the tile
+        if (lay.leader && tlane == 0) {
+            s_node[slot] = e.node;
+            s_state[slot] = (first && s_last[slot] != 0) ? 1 : (lay.team == 0 ? 2 : 3);
+        }
+        __syncthreads();
+
+        // ---- Update: rows of the tile times W
+        for (int rt = rt_first; rt * 16 < nslots; rt += rt_step) {
+            const float *arow = s_A + (size_t)(16 * rt + lrow) * LDA;
+            f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                        for (int j = 0; j < VEC; ++j) atomicAdd(&srow[d + j], acc[c][j]);
+            for (int s = 0; s < NS; ++s) {
+                const int k = 16 * s + 4 * lk;
+                const float4 a4 = *reinterpret_cast<const float4 *>(arow + k);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, wcol[(k + 0) * LDW], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, wcol[(k + 1) * LDW], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, wcol[(k + 2) * LDW], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, wcol[(k + 3) * LDW], acc, 0, 0, 0);
+            }
+            if (col < M) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int r = 16 * rt + 4 * lk + i;  // result row -> slot
+                    if (r < nslots) {
+                        const int st = s_state[r];
+                        if (st == 1) {
+                            fp.out[(size_t)s_node[r] * M + col] = act_bias(acc[i], bcol, fp.relu);
+                        } else if (st >= 2) {
+                            __hip_atomic_store(p.part_rows + ((size_t)tile * 2 + (st - 2)) * M + col, acc[i],
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
                     }
                 }
             }
         }
-        if (seg_head && tlane == 0) {
-            if (cur.leader) s_node[sb * T + cur.slot] = e.node;
-            const int fl = (cur.leader && first ? 1 : 0) | (lastflag != 0 ? 2 : 0);
-            if (fl) atomicOr(&s_flag[sb * T + cur.slot], fl);
-        }
-        __syncthreads();
 
-        multiply_and_store(sb, cur.nslots);
-        if (it > 0) clear_tile(sb_prev, prev_rows);  // everyone finished reading it before this barrier
-        prev_rows = cur.nslots;
-
-        commit_idx(nxt, buf ^ 1);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        cur = nxt;
-        tl_next = tl_after;
-    }
-
-    // rows without any entry: out = act((1+eps) x W + b), sixteen-row tiles through the same MFMA path.
-    // Buffers 0..2 are reused as one scratch tile of up to T rows (buffer 0), after a barrier.
-    __syncthreads();
-    clear_tile(0, T);
-    clear_tile(1, T);
-    clear_tile(2, T);
-    __syncthreads();
-    const int64_t nchunks = ((int64_t)p.n + 63) / 64;
-    const int nteams = nwaves * G, team = wave * G + team_in_wave;
-    for (int64_t c = b; c < nchunks; c += B) {
-        // wave 0 lists the empty nodes of this 64-node chunk
-        if (wave == 0) {
-            const int64_t v = c * 64 + lane;
-            const bool empty = v < p.n && p.ngptr[v] == p.ngptr[v + 1];
-            const unsigned long long m = __ballot(empty);
-            if (empty) s_list[1 + __popcll(m & ((1ull << lane) - 1ull))] = lane;
-            if (lane == 0) s_list[0] = __popcll(m);
-        }
-        __syncthreads();
-        const int cnt = s_list[0];
-        for (int base = 0; base < cnt; base += T) {
-            const int rows = cnt - base < T ? cnt - base : T;
-            for (int r = team; r < rows; r += nteams) {
-                const int64_t node = c * 64 + s_list[1 + base + r];
-                for (int cc = 0; cc < p.iter_total; ++cc) {
-                    const int d = (cc * dwl + tlane) * VEC;
-                    if (d >= dim) break;
-                    float xs[VEC];
-                    load_vec<VEC>(xs, p.X + (size_t)node * dim + d);
+        // ---- ordered flush of the (at most two) unfinished nodes: slot 0 and the last slot
+        const bool part0 = s_state[0] == 2, part1 = s_state[nslots - 1] == 3;
+        if (part0 || part1) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the partial rows have left this wave
+            __syncthreads();                                   // ... and every other wave of the block
+            if (wave == 0) {
+                for (int which = 0; which < 2; ++which) {
+                    if (which == 0 ? !part0 : !part1) continue;
+                    const int node = s_node[which == 0 ? 0 : nslots - 1];
+                    int arrived = 0;
+                    if (lane == 0) arrived = atomicAdd(&p.cnt[node], 1);
+                    arrived = __shfl(arrived, 0);
+                    const int gfirst = p.ngptr[node], gend = p.ngptr[node + 1];
+                    const int64_t b0 = gfirst / T, b1 = (gend - 1) / T;
+                    if (arrived != (int)(b1 - b0)) continue;
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                    if (lane == 0) p.cnt[node] = 0;
+                    if (lane < M) {
+                        // in its first tile the node is the tile's first node only if it starts the tile
+                        float sum = __hip_atomic_load(
+                            p.part_rows + ((size_t)b0 * 2 + (gfirst % T == 0 ? 0 : 1)) * M + lane, __ATOMIC_RELAXED,
+                            __HIP_MEMORY_SCOPE_AGENT);
+                        for (int64_t b = b0 + 1; b <= b1; b += 4) {
+                            float t[4];
 #pragma unroll
-                    for (int j = 0; j < VEC; ++j) s_A[(size_t)r * LDA + d + j] = p.self_scale * xs[j];
-                }
-                if (tlane == 0) {
-                    s_node[r] = (int)node;
-                    s_flag[r] = 3;
+                            for (int q = 0; q < 4; ++q) {
+                                t[q] = 0.0f;
+                                if (b + q <= b1)
+                                    t[q] = __hip_atomic_load(p.part_rows + ((size_t)(b + q) * 2) * M + lane,
+                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            }
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                if (b + q <= b1) sum += t[q];
+                        }
+                        const float bl = fp.b ? fp.b[lane] : 0.0f;
+                        fp.out[(size_t)node * M + lane] = act_bias(sum, bl, fp.relu);
+                    }
                 }
             }
-            __syncthreads();
-            multiply_and_store(0, rows);
-            __syncthreads();
         }
-        __syncthreads();
     }
 }
 
@@ -346,64 +405,47 @@ static const void *fused_fn(int iter, int ns)
     }
 }
 
-// Step groups (of 16) to which K is padded, or 0 if the fused kernel does not cover this shape.
-static int fused_ns(int K)
-{
-    if (K <= 16) return 1;
-    if (K <= 32) return 2;
-    if (K <= 64) return 4;
-    if (K <= 128) return 8;
-    return 0;
-}
-
-// Tries the fused GIN layer.  Returns GNN_OK after enqueueing it, 1 if the shape or the launch
-// shape is outside what it covers (the caller then runs aggregation and GEMM separately), < 0 on error.
+// Tries the fused GIN layer.  Returns GNN_OK after enqueueing it, 1 if the shape is outside what it
+// covers (the caller then runs aggregation and GEMM separately), < 0 on error.  p.part_rows must
+// point to room for 2 * tiles rows of max(K, M) floats.
 int try_gin_layer_fused(AggParams &p, int vec, int wpb, const float *W, const float *b, float *out, int M, int relu,
-                        int64_t tiles_upper, bool force, hipStream_t s)
+                         int64_t tiles_upper, hipStream_t s)
 {
     const int K = p.dim;
-    const int ns = fused_ns(K);
-    const int T = p.T, G = 64 >> p.dwl_log2;
-    if (vec != 4 || ns == 0 || M > 64 || T > 64 || T % 16 != 0) return 1;
-    if ((int64_t)G * p.ngs > 64 * kPipeIdxLoads) return 1;
+    const int ns = K <= 16 ? 1 : (K <= 32 ? 2 : (K <= 64 ? 4 : (K <= 128 ? 8 : 0)));
+    const int T = p.T;
+    if (vec != 4 || ns == 0 || M > 64 || T > 64 || !p.part_rows) return 1;
     const int ct = (M + 15) / 16;
-    if (wpb % ct != 0 || wpb > 4) return 1;  // the kernel is compiled for blocks of up to 4 waves
+    if (wpb > 8 || wpb % ct != 0) return 1;
     if (p.iter_total > 4) return 1;
     if (((uintptr_t)W | (uintptr_t)out) % 4 != 0) return 1;
-    const int lda = 16 * ns + 4;
-    const size_t lds = (size_t)3 * T * lda * 4 + (size_t)6 * T * 4 + (size_t)2 * wpb * G * p.ngs * 4 + 65 * 4;
+    const int kp = 16 * ns, lda = kp + 4, ldw = 16 * ct + 4;
+    const int a_rows = (T + 15) / 16 * 16;  // whole 16-row MFMA tiles
+    size_t lds = (size_t)(kMaxWavesPerBlock + 3 * T + (size_t)T * p.ngs) * 4;
+    lds = (lds + 15) & ~(size_t)15;
+    lds += ((size_t)kp * ldw + (size_t)a_rows * lda + (size_t)wpb * 64) * 4;
     if (lds > kMaxLdsBytes) return 1;
-    const void *fn = fused_fn(p.iter_total, ns);
-    int dev = 0, cus = 0, per_cu = 0;
-    GNN_HIP_TRY(hipGetDevice(&dev));
-    GNN_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    GNN_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, wpb * 64, lds));
-    if (per_cu < 1) return 1;
-    int64_t blocks = (int64_t)per_cu * cus;
-    (void)force;
-    if (blocks > tiles_upper) blocks = tiles_upper > 0 ? tiles_upper : 1;
-    if (blocks >= kNumXcd) blocks = blocks / kNumXcd * kNumXcd;
-    // rows of `out` that will receive atomic adds are zeroed first; rows without entries are written
-    // by the fused kernel itself
-    AggParams po = p;
-    po.out = out;
-    po.dim = M;
-    po.bias = b;
-    po.relu = relu;
-    po.do_empty = 1;
-    launch_agg_init(po, false, s);
+
+    const int64_t grid = tiles_upper;
+    const int64_t nchunks = ((int64_t)p.n + 63) / 64;
+    int64_t extra = (nchunks + (int64_t)wpb * 8 - 1) / ((int64_t)wpb * 8);
+    if (extra > 4096) extra = 4096;
+    if (grid + extra >= ((int64_t)1 << 31)) return GNN_ELIMIT;
+
     FusedParams fp;
     fp.a = p;
+    fp.a.tile_blocks = grid;
+    fp.a.extra_blocks = (int)extra;
     fp.W = W;
     fp.b = b;
     fp.out = out;
     fp.M = M;
     fp.relu = relu;
     fp.ct = ct;
+    fp.a_rows = a_rows;
+    const void *fn = fused_fn(p.iter_total, ns);
     void *args[] = {(void *)&fp};
-    GNN_HIP_TRY(hipLaunchKernel(fn, dim3((unsigned)blocks), dim3((unsigned)(wpb * 64)), args, lds, s));
-    if (b || relu) launch_agg_epilogue_spanning(po, s);
-    GNN_HIP_TRY(hipGetLastError());
+    GNN_HIP_TRY(hipLaunchKernel(fn, dim3((unsigned)(grid + extra)), dim3((unsigned)(wpb * 64)), args, lds, s));
     return GNN_OK;
 }
 

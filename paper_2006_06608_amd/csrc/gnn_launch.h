@@ -46,10 +46,11 @@ int pipe_blocks(int vec, int iter, bool weighted, bool self, int cus, int wpb, s
 int launch_aggregate_pipe(int vec, int iter, bool weighted, bool self, int blocks, int wpb, size_t lds, hipStream_t s,
                           AggParams &p);
 
-// gnn_gin_fused.hip: GIN aggregation with the Update fused in.  Returns GNN_OK when the fused kernel
-// was launched, 1 when the shape does not qualify (nothing launched), < 0 on error.
+// gnn_gin_fused.hip: GIN aggregation with the Update fused in, on the general kernel with the ordered
+// flush; p.part_rows must have room for rows of max(p.dim, M) floats.  Returns GNN_OK when the fused
+// kernel was launched, 1 when the shape does not qualify (nothing launched), < 0 on error.
 int try_gin_layer_fused(AggParams &p, int vec, int wpb, const float *W, const float *b, float *out, int M, int relu,
-                        int64_t tiles_upper, bool force, hipStream_t s);
+                        int64_t tiles_upper, hipStream_t s);
 
 // gnn_update.hip: out[n,M] = act(A[n,K] W[K,M] + b) on the MFMA units.
 int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b, int relu,

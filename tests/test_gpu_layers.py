@@ -246,3 +246,28 @@ def test_widening_gcn_layer_may_aggregate_first():
         torch.cuda.synchronize()
         res.append(out.cpu().numpy())
     assert np.array_equal(res[0].view(np.uint32), res[1].view(np.uint32))
+
+
+def test_fusion_is_automatic_for_short_rows_and_can_be_switched_off():
+    """A GIN layer on a batch of small graphs (mean row < 8) runs fused by itself; GNN_FLAG_NO_FUSION
+    gives the two separate kernels.  Both match the oracle; rows complete inside one block (all of
+    them here) see the same arithmetic either way up to the order of the MFMA steps."""
+    g = config_graph(3, shrink=4)
+    K, M = 64, 64
+    X = features(g.n, K, seed=301)
+    W = glorot(K, M, seed=302)
+    b = features(1, M, seed=303)[0] * 0.1
+    ref, scale = oracle.gin_layer(g.rowptr, g.colidx, 0.0, X, W, b, True, want_abs=True)
+    G = DeviceGraph(g.rowptr, g.colidx)
+    ws = gnn.alloc_workspace(G.n, G.nnz, 64, 0)
+    outs = []
+    for flags in (0, gnn.GNN_FLAG_NO_FUSION, gnn.GNN_FLAG_FUSION, gnn.GNN_FLAG_DETERMINISTIC):
+        out = torch.full((G.n, M), float("nan"), device="cuda")
+        gnn.gnn_layer_forward(gnn.GNN_GIN, G.n, G.nnz, G.rowptr, G.colidx, None, 0.0, dev(X), K, dev(W), dev(b), M, True, out,
+                              0, 0, 0, flags, ws)
+        torch.cuda.synchronize()
+        gnn.gnn_workspace_status(ws)
+        outs.append(out.cpu().numpy())
+        assert_parity(outs[-1], ref, scale, f"gin layer flags {flags}")
+    assert np.array_equal(outs[0].view(np.uint32), outs[2].view(np.uint32))  # automatic == requested fusion
+    assert np.array_equal(outs[0].view(np.uint32), outs[3].view(np.uint32))  # the fused kernel is deterministic
