@@ -560,7 +560,12 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     const bool kernel_chosen = (flags & (GNN_FLAG_PIPELINE | GNN_FLAG_NO_PIPELINE | GNN_FLAG_XCD_RUNS)) != 0;
     if (fuse && !atomic_flush && !(flags & GNN_FLAG_NO_FUSION) &&
         ((flags & GNN_FLAG_FUSION) || (avg_row < 8.0 && !kernel_chosen))) {
-        const int wpb_f = auto_wpb ? 8 : wpb;  // large tiles amortise the copy of W every block makes
+        // large tiles (up to 64 groups) amortise the copy of W every block makes
+        int wpb_f = wpb;
+        if (auto_wpb) {
+            wpb_f = 8;
+            while (wpb_f > 1 && wpb_f * (64 >> dwl_log2) > 64) wpb_f /= 2;
+        }
         AggParams pf = p;
         pf.T = wpb_f * (64 >> dwl_log2);
         const int32_t part_dim = fuse->M > dim ? fuse->M : dim;  // fused partial rows are M wide
