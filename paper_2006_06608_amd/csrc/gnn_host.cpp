@@ -163,14 +163,15 @@ void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, in
     (void)max_degree;
     const double avg = n > 0 ? (double)nnz / (double)n : 0.0;
     // dimension workers: lanes per neighbor row.  Each lane moves `vec` floats per load and owns up
-    // to 4 chunks of the row.  A lane should have about 8 independent loads in flight; a row with
-    // fewer than 8 neighbors cannot supply them from one chunk, so with short rows a lane takes at
-    // least two chunks (measured on batches of small graphs: 25 % faster at Dim 64).  Among the
+    // to 4 chunks of the row.  A lane should have about 8 independent loads in flight; a row of at
+    // most 4 neighbors supplies them in one batch only if the lane takes two chunks (a two-chunk lane
+    // batches 4 neighbors; measured on batches of small graphs: 25 % faster at Dim 64, while rows of
+    // 5..8 neighbors would need a second batch and gain nothing).  Among the
     // admissible powers of two take the one that leaves the fewest lane slots idle
     // (dw * chunks - row length in vectors), and among equals the widest team (fewest chunks).
     if (*dw <= 0) {
         const int units = (dim + vec - 1) / vec;
-        const int min_chunks = (avg < 8.0 && units >= 2) ? 2 : 1;
+        const int min_chunks = (avg <= 4.0 && units >= 2) ? 2 : 1;
         int best = 64, best_waste = 1 << 30;
         for (int d = 1; d <= 64; d *= 2) {
             const int chunks = (units + d - 1) / d;
