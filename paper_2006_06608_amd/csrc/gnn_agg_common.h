@@ -141,13 +141,33 @@ __device__ __forceinline__ T load_stream(const T *p)
 #endif
 }
 
+// The header words a kernel checks before it trusts the partition, read in one go.
+struct HeaderVals {
+    uint32_t magic;
+    int32_t n, ngs, status;
+    int64_t nnz, num_ng;
+};
+
+__device__ __forceinline__ HeaderVals load_header(const WsHeader *hdr)
+{
+    HeaderVals h;
+    h.magic = hdr->magic;
+    h.n = hdr->n;
+    h.ngs = hdr->ngs;
+    h.status = hdr->status;
+    h.nnz = hdr->nnz;
+    h.num_ng = hdr->num_ng;
+    return h;
+}
+
+__device__ __forceinline__ bool header_vals_ok(const HeaderVals &h, const AggParams &p)
+{
+    return (h.magic == kMagic) & (h.status == GNN_OK) & (h.ngs == p.ngs) & (h.n == p.n) & (h.nnz == p.nnz);
+}
+
 __device__ __forceinline__ bool header_ok(const WsHeader *hdr, const AggParams &p)
 {
-    // all fields are read at once (no short-circuit: one round trip instead of five)
-    const uint32_t magic = hdr->magic;
-    const int32_t n = hdr->n, ngs = hdr->ngs, status = hdr->status;
-    const int64_t nnz = hdr->nnz;
-    return (magic == kMagic) & (status == GNN_OK) & (ngs == p.ngs) & (n == p.n) & (nnz == p.nnz);
+    return header_vals_ok(load_header(hdr), p);
 }
 
 // The workspace does not hold the partition the launch was prepared for: record why nothing was

@@ -103,13 +103,23 @@ void k_aggregate(AggParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const WsHeader *hdr = p.hdr;
-    if (!header_ok(hdr, p)) {
+    const int T = p.T;
+    int64_t tile = blockIdx.x;
+    if (p.xcd_remap) {
+        // Blocks are dealt to the eight XCDs round-robin by index.  Give every XCD runs of kXcdRun
+        // consecutive tiles (neighbouring node ids, hence shared neighbours after renumbering, meet
+        // in one L2) while the runs themselves still interleave over the XCDs, which keeps the
+        // load balanced.
+        const int64_t x = blockIdx.x % kNumXcd, q = blockIdx.x / kNumXcd;
+        tile = ((q / kXcdRun) * kNumXcd + x) * kXcdRun + q % kXcdRun;
+    }
+    const HeaderVals hv = load_header(hdr);
+    if (!header_vals_ok(hv, p)) {
         // with the ordered flush no kernel runs before this one: record why nothing was computed
         if (p.part_rows && blockIdx.x == 0 && threadIdx.x == 0) note_stale(p.hdr, p);
         return;
     }
 
-    const int T = p.T;
     if ((int64_t)blockIdx.x >= p.tile_blocks) {
         // blocks appended to the grid: rows without entries (independent of every tile)
         const int nw = blockDim.x >> 6, wv = threadIdx.x >> 6;
@@ -120,17 +130,8 @@ void k_aggregate(AggParams p)
         write_empty_rows<VEC, SELF>(p, eb * nw + wv, (int64_t)p.extra_blocks * nw, s_list + wv * 64);
         return;
     }
-    const int64_t num_ng = hdr->num_ng;
+    const int64_t num_ng = hv.num_ng;
     const int64_t tiles = (num_ng + T - 1) / T;
-    int64_t tile = blockIdx.x;
-    if (p.xcd_remap) {
-        // Blocks are dealt to the eight XCDs round-robin by index.  Give every XCD runs of kXcdRun
-        // consecutive tiles (neighbouring node ids, hence shared neighbours after renumbering, meet
-        // in one L2) while the runs themselves still interleave over the XCDs, which keeps the
-        // load balanced.
-        const int64_t x = blockIdx.x % kNumXcd, q = blockIdx.x / kNumXcd;
-        tile = ((q / kXcdRun) * kNumXcd + x) * kXcdRun + q % kXcdRun;
-    }
     if (tile >= tiles) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
