@@ -11,7 +11,7 @@ __all__ = [
     "GnnError", "lib_path", "load", "exported_symbols",
     "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_XCD_RUNS", "GNN_FLAG_NO_PIPELINE",
     "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_FLAG_NO_FUSION", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
-    "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall",
+    "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall", "AggregateCall",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
@@ -280,6 +280,30 @@ def gnn_aggregate_gin(n, nnz, rowptr, colidx, eps, X, out, dim, ngs=0, dw=0, wav
                                   _f32(eps), _dev(X, "float32", "X"), _dev(out, "float32", "out"), _i32(dim),
                                   _i32(ngs), _i32(dw), _i32(waves_per_block), _u32(flags), wp, wb, _stream(stream))
     _check(rc, "gnn_aggregate_gin")
+
+
+class AggregateCall:
+    """Arguments of gnn_aggregate_gcn (eps None; ew a tensor or None) or gnn_aggregate_gin (eps a number)
+    marshalled once, for repeated calls on the same tensors: agg = AggregateCall(...); agg() enqueues one
+    aggregation on the stream given here (or on the current one)."""
+
+    def __init__(self, n, nnz, rowptr, colidx, ew, eps, X, out, dim, ngs=0, dw=0, waves_per_block=0, flags=0,
+                 workspace=None, stream=None):
+        if eps is not None and ew is not None:
+            raise ValueError("GIN aggregation takes no edge weights")
+        self._keep = (rowptr, colidx, ew, X, out, workspace)
+        wp, wb = _ws(workspace)
+        gin = eps is not None
+        self._what = "gnn_aggregate_gin" if gin else "gnn_aggregate_gcn"
+        self._fn = getattr(load(), self._what)
+        self._stream = stream
+        self._args = [_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"), _dev(colidx, "int32", "colidx"),
+                      _f32(eps) if gin else _dev(ew, "float32", "ew"), _dev(X, "float32", "X"),
+                      _dev(out, "float32", "out"), _i32(dim), _i32(ngs), _i32(dw), _i32(waves_per_block), _u32(flags),
+                      wp, wb]
+
+    def __call__(self):
+        _check(self._fn(*self._args, _stream(self._stream)), self._what)
 
 
 def gnn_aggregate_reduce(op, n, nnz, rowptr, colidx, X, out, dim, ngs=0, dw=0, waves_per_block=0, flags=0,

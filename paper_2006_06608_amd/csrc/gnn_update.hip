@@ -14,10 +14,10 @@ namespace gnn {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kGemmRows = 64;   // rows of A per tile (4 waves x 16)
-constexpr int kGemmKC = 32;     // K chunk staged per step
-constexpr int kGemmLda = kGemmKC + 4;
+constexpr int kGemmRows = 64;        // rows of A per tile (4 waves x 16)
+constexpr int kGemmKC = 32;          // K chunk staged per step
 constexpr int kGemmWFloats = 12288;  // LDS floats available for the W slice (48 KB)
+constexpr int kGemmFewRows = 65536;  // below this many rows every block of the grid gets at most one 64-row tile
 
 struct GemmParams {
     const float *A;
@@ -31,38 +31,45 @@ struct GemmParams {
     int relu;
 };
 
+// MT: 16-column tiles per wave.
 template <int MT, bool VEC4>
 __global__ __launch_bounds__(256) void k_update_gemm(GemmParams p)
 {
+    constexpr int KC = kGemmKC, ROWS = kGemmRows, NT = 256;
     extern __shared__ __align__(16) float smem_f[];
     constexpr int MP = 16 * MT;
     constexpr int LDW = MP + 4;
+    constexpr int LDA = KC + 4;
+    constexpr int F4 = ROWS * KC / 4 / NT;   // float4 loads per thread and chunk
+    constexpr int RSTEP4 = NT / (KC / 4);    // rows covered by one pass of float4 loads
+    constexpr int F1 = ROWS * KC / NT;       // scalar loads per thread and chunk
+    static_assert(NT % (KC / 4) == 0 && (ROWS * KC) % (4 * NT) == 0, "tile shape");
     const int kslice = p.k_end - p.k_begin;
-    const int kpad = (kslice + kGemmKC - 1) / kGemmKC * kGemmKC;
+    const int kpad = (kslice + KC - 1) / KC * KC;
     float *s_W = smem_f;                      // [kpad][LDW]
-    float *s_A = smem_f + (size_t)kpad * LDW;  // [64][kGemmLda]
+    float *s_A = smem_f + (size_t)kpad * LDW;  // [ROWS][LDA]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col0 = blockIdx.y * MP;
 
-    const int64_t ntiles = ((int64_t)p.n + kGemmRows - 1) / kGemmRows;
+    const int64_t ntiles = ((int64_t)p.n + ROWS - 1) / ROWS;
     const int lrow = lane & 15, lk = lane >> 4;
     bool w_staged = false;
 
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t row0 = tile * kGemmRows;
+        const int64_t row0 = tile * ROWS;
         f32x4 acc[MT];
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
         // prefetch registers for one K chunk of the A tile
-        float4 pre4[2];
-        float pre1[8];
+        float4 pre4[VEC4 ? F4 : 1];
+        float pre1[VEC4 ? 1 : F1];
         auto fetch = [&](int kc) {
             if constexpr (VEC4) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const int r = (tid >> 3) + 32 * i, c = (tid & 7) * 4;
+                for (int i = 0; i < F4; ++i) {
+                    const int r = tid / (KC / 4) + RSTEP4 * i, c = (tid % (KC / 4)) * 4;
                     const int64_t row = row0 + r;
                     const int k = p.k_begin + kc + c;
                     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -71,8 +78,9 @@ __global__ __launch_bounds__(256) void k_update_gemm(GemmParams p)
                 }
             } else {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int r = (tid >> 5) + 8 * i, c = tid & 31;
+                for (int i = 0; i < F1; ++i) {
+                    const int e = tid + NT * i;
+                    const int r = e / KC, c = e % KC;
                     const int64_t row = row0 + r;
                     const int k = p.k_begin + kc + c;
                     pre1[i] = (row < p.n && k < p.k_end) ? p.A[(size_t)row * p.K + k] : 0.0f;
@@ -82,15 +90,15 @@ __global__ __launch_bounds__(256) void k_update_gemm(GemmParams p)
         auto commit = [&]() {
             if constexpr (VEC4) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const int r = (tid >> 3) + 32 * i, c = (tid & 7) * 4;
-                    *reinterpret_cast<float4 *>(&s_A[r * kGemmLda + c]) = pre4[i];
+                for (int i = 0; i < F4; ++i) {
+                    const int r = tid / (KC / 4) + RSTEP4 * i, c = (tid % (KC / 4)) * 4;
+                    *reinterpret_cast<float4 *>(&s_A[r * LDA + c]) = pre4[i];
                 }
             } else {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int r = (tid >> 5) + 8 * i, c = tid & 31;
-                    s_A[r * kGemmLda + c] = pre1[i];
+                for (int i = 0; i < F1; ++i) {
+                    const int e = tid + NT * i;
+                    s_A[(e / KC) * LDA + e % KC] = pre1[i];
                 }
             }
         };
@@ -98,32 +106,54 @@ __global__ __launch_bounds__(256) void k_update_gemm(GemmParams p)
         fetch(0);
         if (!w_staged) {  // after the first A loads are in flight; visible after the barrier below
             w_staged = true;
-            // W slice -> LDS, zero padded (16-byte loads when the slice is a whole number of float4s)
+            // W slice -> LDS, zero padded (16-byte loads when the slice is a whole number of float4s);
+            // two loads per thread are issued before the first is stored (more cost registers, hence resident blocks)
+            constexpr int WB = 2;
             if (p.M % 4 == 0 && ((uintptr_t)p.W & 15) == 0) {
                 constexpr int MQ = MP / 4;
-                for (int i = tid; i < kpad * MQ; i += 256) {
-                    const int k = i / MQ, c = (i % MQ) * 4;
-                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (k < kslice && col0 + c < p.M) v = *reinterpret_cast<const float4 *>(p.W + (size_t)(p.k_begin + k) * p.M + col0 + c);
-                    *reinterpret_cast<float4 *>(&s_W[k * LDW + c]) = v;
+                const int total = kpad * MQ;
+                for (int base = tid; base < total; base += NT * WB) {
+                    float4 v[WB];
+#pragma unroll
+                    for (int j = 0; j < WB; ++j) {
+                        const int i = base + j * NT;
+                        const int k = i / MQ, c = (i % MQ) * 4;
+                        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (i < total && k < kslice && col0 + c < p.M)
+                            v[j] = *reinterpret_cast<const float4 *>(p.W + (size_t)(p.k_begin + k) * p.M + col0 + c);
+                    }
+#pragma unroll
+                    for (int j = 0; j < WB; ++j) {
+                        const int i = base + j * NT;
+                        if (i < total) *reinterpret_cast<float4 *>(&s_W[(i / MQ) * LDW + (i % MQ) * 4]) = v[j];
+                    }
                 }
             } else {
-                for (int i = tid; i < kpad * MP; i += 256) {
-                    const int k = i / MP, c = i % MP;
-                    float v = 0.0f;
-                    if (k < kslice && col0 + c < p.M) v = p.W[(size_t)(p.k_begin + k) * p.M + col0 + c];
-                    s_W[k * LDW + c] = v;
+                const int total = kpad * MP;
+                for (int base = tid; base < total; base += NT * WB) {
+                    float v[WB];
+#pragma unroll
+                    for (int j = 0; j < WB; ++j) {
+                        const int i = base + j * NT;
+                        const int k = i / MP, c = i % MP;
+                        v[j] = (i < total && k < kslice && col0 + c < p.M) ? p.W[(size_t)(p.k_begin + k) * p.M + col0 + c] : 0.0f;
+                    }
+#pragma unroll
+                    for (int j = 0; j < WB; ++j) {
+                        const int i = base + j * NT;
+                        if (i < total) s_W[(i / MP) * LDW + i % MP] = v[j];
+                    }
                 }
             }
         }
-        for (int kc = 0; kc < kpad; kc += kGemmKC) {
+        for (int kc = 0; kc < kpad; kc += KC) {
             __syncthreads();  // previous chunk fully consumed (and, first time, W staged)
             commit();
             __syncthreads();
-            if (kc + kGemmKC < kpad) fetch(kc + kGemmKC);
-            const float *arow = &s_A[(wave * 16 + lrow) * kGemmLda];
+            if (kc + KC < kpad) fetch(kc + KC);
+            const float *arow = &s_A[(wave * 16 + lrow) * LDA];
 #pragma unroll
-            for (int ks = 0; ks < kGemmKC; ks += 16) {
+            for (int ks = 0; ks < KC; ks += 16) {
                 const float4 a4 = *reinterpret_cast<const float4 *>(arow + ks + 4 * lk);
                 const float av[4] = {a4.x, a4.y, a4.z, a4.w};
                 const float *wrow = &s_W[(kc + ks + 4 * lk) * LDW + lrow];
@@ -157,6 +187,135 @@ __global__ __launch_bounds__(256) void k_update_gemm(GemmParams p)
                         *o = v;
                     }
                 }
+            }
+        }
+    }
+}
+
+// Few rows (at most one 64-row tile per block) and K >= 128: nothing is gained by keeping W in LDS
+// for the life of the block, so the W rows of each K chunk travel with the A chunk (registers, then
+// LDS), any K is one launch, and the chunk is wide (128, or 64 for 64 columns) so that a block has
+// enough bytes in flight.  2,708 x 1,433 x 16: 32 us (three launches of the kernel above) before.
+template <int MT, bool VEC4, bool WV4, int KC>
+__global__ __launch_bounds__(256) void k_update_gemm_few(GemmParams p)
+{
+    extern __shared__ __align__(16) float smem_f[];
+    constexpr int MP = 16 * MT, LDW = MP + 4, LDA = KC + 4, NT = 256;
+    constexpr int F4 = 64 * KC / 4 / NT, RSTEP4 = NT / (KC / 4), F1 = 64 * KC / NT;
+    constexpr int MQ = MP / 4, W4 = KC * MQ / NT, W1 = KC * MP / NT;
+    static_assert((KC * MQ) % NT == 0 && NT % (KC / 4) == 0, "chunk shape");
+    float *s_W = smem_f;             // [KC][LDW]
+    float *s_A = smem_f + KC * LDW;  // [64][LDA]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col0 = blockIdx.y * MP;
+    const int lrow = lane & 15, lk = lane >> 4;
+    const int64_t row0 = (int64_t)blockIdx.x * 64;
+    const int kpad = (p.K + KC - 1) / KC * KC;
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    float4 a4r[VEC4 ? F4 : 1], w4r[WV4 ? W4 : 1];
+    float a1r[VEC4 ? 1 : F1], w1r[WV4 ? 1 : W1];
+    auto fetch = [&](int kc) {
+        if constexpr (VEC4) {
+#pragma unroll
+            for (int i = 0; i < F4; ++i) {
+                const int r = tid / (KC / 4) + RSTEP4 * i, c = (tid % (KC / 4)) * 4;
+                const int64_t row = row0 + r;
+                const int k = kc + c;
+                a4r[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (row < p.n && k < p.K) a4r[i] = *reinterpret_cast<const float4 *>(p.A + (size_t)row * p.K + k);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < F1; ++i) {
+                const int e = tid + NT * i;
+                const int64_t row = row0 + e / KC;
+                const int k = kc + e % KC;
+                a1r[i] = (row < p.n && k < p.K) ? p.A[(size_t)row * p.K + k] : 0.0f;
+            }
+        }
+        if constexpr (WV4) {
+#pragma unroll
+            for (int j = 0; j < W4; ++j) {
+                const int i = tid + NT * j;
+                const int k = kc + i / MQ, c = col0 + (i % MQ) * 4;
+                w4r[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (k < p.K && c < p.M) w4r[j] = *reinterpret_cast<const float4 *>(p.W + (size_t)k * p.M + c);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < W1; ++j) {
+                const int i = tid + NT * j;
+                const int k = kc + i / MP, c = col0 + i % MP;
+                w1r[j] = (k < p.K && c < p.M) ? p.W[(size_t)k * p.M + c] : 0.0f;
+            }
+        }
+    };
+    auto commit = [&]() {
+        if constexpr (VEC4) {
+#pragma unroll
+            for (int i = 0; i < F4; ++i) {
+                const int r = tid / (KC / 4) + RSTEP4 * i, c = (tid % (KC / 4)) * 4;
+                *reinterpret_cast<float4 *>(&s_A[r * LDA + c]) = a4r[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < F1; ++i) {
+                const int e = tid + NT * i;
+                s_A[(e / KC) * LDA + e % KC] = a1r[i];
+            }
+        }
+        if constexpr (WV4) {
+#pragma unroll
+            for (int j = 0; j < W4; ++j) {
+                const int i = tid + NT * j;
+                *reinterpret_cast<float4 *>(&s_W[(i / MQ) * LDW + (i % MQ) * 4]) = w4r[j];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < W1; ++j) {
+                const int i = tid + NT * j;
+                s_W[(i / MP) * LDW + i % MP] = w1r[j];
+            }
+        }
+    };
+
+    fetch(0);
+    for (int kc = 0; kc < kpad; kc += KC) {
+        __syncthreads();  // previous chunk fully consumed
+        commit();
+        __syncthreads();
+        if (kc + KC < kpad) fetch(kc + KC);
+        const float *arow = &s_A[(wave * 16 + lrow) * LDA];
+#pragma unroll
+        for (int ks = 0; ks < KC; ks += 16) {
+            const float4 a4 = *reinterpret_cast<const float4 *>(arow + ks + 4 * lk);
+            const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+            const float *wrow = &s_W[(ks + 4 * lk) * LDW + lrow];
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s4], wrow[s4 * LDW + t * 16], acc[t], 0, 0, 0);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const int col = col0 + t * 16 + lrow;
+        if (col < p.M) {
+            const float bc = p.b ? p.b[col] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t row = row0 + wave * 16 + 4 * lk + i;
+                float v = acc[t][i] + bc;
+                if (p.relu) v = fmaxf(v, 0.0f);
+                if (row < p.n) p.out[(size_t)row * p.M + col] = v;
             }
         }
     }
@@ -248,6 +407,16 @@ static void launch_gemm(bool vec4, dim3 grid, size_t lds, hipStream_t s, const G
     else hipLaunchKernelGGL((k_update_gemm<MT, false>), grid, dim3(256), lds, s, p);
 }
 
+template <int MT, int KC>
+static void launch_gemm_few(bool vec4, bool wv4, dim3 grid, hipStream_t s, const GemmParams &p)
+{
+    const size_t lds = ((size_t)KC * (16 * MT + 4) + (size_t)64 * (KC + 4)) * sizeof(float);
+    if (vec4 && wv4) hipLaunchKernelGGL((k_update_gemm_few<MT, true, true, KC>), grid, dim3(256), lds, s, p);
+    else if (vec4) hipLaunchKernelGGL((k_update_gemm_few<MT, true, false, KC>), grid, dim3(256), lds, s, p);
+    else if (wv4) hipLaunchKernelGGL((k_update_gemm_few<MT, false, true, KC>), grid, dim3(256), lds, s, p);
+    else hipLaunchKernelGGL((k_update_gemm_few<MT, false, false, KC>), grid, dim3(256), lds, s, p);
+}
+
 int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b, int relu,
                      float *out, hipStream_t s)
 {
@@ -272,11 +441,25 @@ int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const floa
         GNN_HIP_TRY(hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(256), args, 0, s));
         return GNN_OK;
     }
+    const bool vec4 = (K % 4 == 0) && ((uintptr_t)A % 16 == 0);
+    const int64_t ntiles = ((int64_t)n + kGemmRows - 1) / kGemmRows;
+    if (n < kGemmFewRows && K >= 128) {  // one tile per block, W travels with A: one launch for any K
+        GemmParams p;
+        p.A = A; p.W = W; p.b = b; p.out = out;
+        p.n = n; p.K = K; p.M = M;
+        p.k_begin = 0; p.k_end = K; p.accumulate = 0; p.finish = 1;
+        p.relu = relu;
+        const bool wv4 = (M % 4 == 0) && ((uintptr_t)W % 16 == 0);
+        const dim3 grid((unsigned)ntiles, (unsigned)((M + MP - 1) / MP));
+        if (MT == 1) launch_gemm_few<1, 128>(vec4, wv4, grid, s, p);
+        else if (MT == 2) launch_gemm_few<2, 128>(vec4, wv4, grid, s, p);
+        else launch_gemm_few<4, 64>(vec4, wv4, grid, s, p);
+        GNN_HIP_TRY(hipGetLastError());
+        return GNN_OK;
+    }
     // K slice whose W rows fit the LDS budget, a multiple of the K chunk
     int kmax = kGemmWFloats / LDW / kGemmKC * kGemmKC;
     if (kmax < kGemmKC) kmax = kGemmKC;
-    const bool vec4 = (K % 4 == 0) && ((uintptr_t)A % 16 == 0);
-    const int64_t ntiles = ((int64_t)n + kGemmRows - 1) / kGemmRows;
     const int64_t gx = ntiles < 1024 ? ntiles : 1024;
     const dim3 grid((unsigned)gx, (unsigned)((M + MP - 1) / MP));
     for (int k0 = 0; k0 < K; k0 += kmax) {
@@ -289,7 +472,7 @@ int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const floa
         p.finish = p.k_end == K;
         p.relu = relu;
         const int kpad = (p.k_end - p.k_begin + kGemmKC - 1) / kGemmKC * kGemmKC;
-        const size_t lds = ((size_t)kpad * LDW + (size_t)kGemmRows * kGemmLda) * sizeof(float);
+        const size_t lds = ((size_t)kpad * LDW + (size_t)kGemmRows * (kGemmKC + 4)) * sizeof(float);
         if (MT == 1) launch_gemm<1>(vec4, grid, lds, s, p);
         else if (MT == 2) launch_gemm<2>(vec4, grid, lds, s, p);
         else launch_gemm<4>(vec4, grid, lds, s, p);

@@ -239,6 +239,28 @@ def test_reuse_partition_gives_identical_results():
     assert_parity(b, ref, ab, "reused")
 
 
+def test_prepared_call_equals_the_plain_call():
+    rp, ci = _graph("rmat")
+    ew = oracle.gcn_norm(rp, ci)
+    G = DeviceGraph(rp, ci, ew)
+    X = features(G.n, 24, seed=6)
+    Xd = dev(X)
+    ws = gnn.alloc_workspace(G.n, G.nnz, 24, 0)
+    for eps, w in ((None, G.ew), (None, None), (0.25, None)):
+        out = torch.full_like(Xd, float("nan"))
+        call = gnn.AggregateCall(G.n, G.nnz, G.rowptr, G.colidx, w, eps, Xd, out, 24, workspace=ws)
+        call()
+        call()  # a prepared call can be repeated
+        torch.cuda.synchronize()
+        if eps is None:
+            ref, ab = oracle.aggregate_gcn(rp, ci, ew if w is not None else None, X, want_abs=True)
+        else:
+            ref, ab = oracle.aggregate_gin(rp, ci, eps, X, want_abs=True)
+        assert_parity(out.cpu().numpy(), ref, ab, f"prepared eps={eps} weighted={w is not None}")
+    with pytest.raises(ValueError):
+        gnn.AggregateCall(G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, Xd, out, 24, workspace=ws)
+
+
 def test_renumbered_graph_gives_the_same_aggregation():
     g = config_graph(4, shrink=32)
     perm, iperm, _, did = gnn.gnn_reorder(g.rowptr, g.colidx)
