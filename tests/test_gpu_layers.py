@@ -272,3 +272,51 @@ def test_fusion_is_automatic_for_short_rows_and_can_be_switched_off():
         assert_parity(outs[-1], ref, scale, f"gin layer flags {flags}")
     assert np.array_equal(outs[0].view(np.uint32), outs[2].view(np.uint32))  # automatic == requested fusion
     assert np.array_equal(outs[0].view(np.uint32), outs[3].view(np.uint32))  # the fused kernel is deterministic
+
+
+@pytest.mark.parametrize("out_dim", [1, 2, 3, 5, 6, 7, 22, 33, 70])
+@pytest.mark.parametrize("flags", [0, gnn.GNN_FLAG_ATOMIC_FLUSH, gnn.GNN_FLAG_DETERMINISTIC, gnn.GNN_FLAG_XCD_RUNS,
+                                   gnn.GNN_FLAG_NO_BLOCK_OPT])
+def test_gcn_layer_with_a_width_that_is_not_a_multiple_of_four(out_dim, flags):
+    # rows of such a width are not 16-byte aligned: the narrow load and store paths; nothing may be
+    # written past the end of `out`
+    g = config_graph(4, shrink=32)
+    ew = oracle.gcn_norm(g.rowptr, g.colidx)
+    G = DeviceGraph(g.rowptr, g.colidx, ew)
+    rng = np.random.default_rng(out_dim)
+    X = features(g.n, 24, seed=3)
+    W = glorot(24, out_dim, seed=out_dim)
+    b = rng.standard_normal(out_dim).astype(np.float32)
+    ref, ab = oracle.gcn_layer(g.rowptr, g.colidx, ew, X, W, b, True, want_abs=True)
+    guard = 64
+    buf = torch.full((g.n * out_dim + guard,), float("nan"), device="cuda")
+    out = buf[: g.n * out_dim].view(g.n, out_dim)
+    ws = gnn.alloc_workspace(g.n, g.nnz, max(24, out_dim), 0)
+    gnn.gnn_layer_forward(gnn.GNN_GCN, g.n, g.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), 24, dev(W), dev(b), out_dim, True,
+                          out, 0, 0, 0, flags, ws)
+    torch.cuda.synchronize()
+    gnn.gnn_workspace_status(ws)
+    assert_parity(out.cpu().numpy(), ref, ab, f"gcn layer 24->{out_dim} flags={flags}")
+    assert torch.isnan(buf[g.n * out_dim:]).all()
+
+
+def test_gcn_layer_in_a_workspace_without_room_for_partial_rows():
+    g = config_graph(4, shrink=32)
+    ew = oracle.gcn_norm(g.rowptr, g.colidx)
+    G = DeviceGraph(g.rowptr, g.colidx, ew)
+    X = features(g.n, 16, seed=4)
+    W = glorot(16, 22, seed=5)
+    ref, ab = oracle.gcn_layer(g.rowptr, g.colidx, ew, X, W, None, False, want_abs=True)
+    out = torch.full((g.n, 22), float("nan"), device="cuda")
+    full = gnn.alloc_workspace(g.n, g.nnz, 22, 16)
+    # keep the intermediate, drop the partial rows: rows that span blocks are finished with atomics
+    tight = full[: gnn.gnn_workspace_bytes(g.n, g.nnz, 0, 16) + ((g.n * 22 * 4 + 255) // 256) * 256]
+    assert tight.numel() < full.numel()
+    with pytest.raises(gnn.GnnError):
+        gnn.gnn_layer_forward(gnn.GNN_GCN, g.n, g.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), 16, dev(W), None, 22, False,
+                              out, 16, 0, 0, gnn.GNN_FLAG_DETERMINISTIC, tight)
+    gnn.gnn_layer_forward(gnn.GNN_GCN, g.n, g.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), 16, dev(W), None, 22, False, out,
+                          16, 0, 0, 0, tight)
+    torch.cuda.synchronize()
+    gnn.gnn_workspace_status(tight)
+    assert_parity(out.cpu().numpy(), ref, ab, "gcn layer 16->22, tight workspace")
