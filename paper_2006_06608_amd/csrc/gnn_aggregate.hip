@@ -131,8 +131,7 @@ void k_aggregate(AggParams p)
         return;
     }
     const int64_t num_ng = hv.num_ng;
-    const int64_t tiles = (num_ng + T - 1) / T;
-    if (tile >= tiles) return;
+    if (tile * T >= num_ng) return;  // (the grid is sized from an upper bound of the group count)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int dwl_log2 = p.dwl_log2, dwl = 1 << dwl_log2;

@@ -79,9 +79,8 @@ void k_gin_layer_fused(FusedParams fp)
     // loop costs registers).  Surplus blocks of the over-sized grid leave before they touch anything.
     const bool tile_block = (int64_t)blockIdx.x < p.tile_blocks;
     const int64_t num_ng = hdr->num_ng;
-    const int64_t tiles = (num_ng + T - 1) / T;
     const int64_t tile = blockIdx.x;
-    if (tile_block && tile >= tiles) return;
+    if (tile_block && tile * T >= num_ng) return;
 
     // W into LDS (zero padded to KP rows and 64 columns): thread t takes the float4 (t mod 16) of the
     // rows t/16, t/16 + blockDim/16, ...; the loads overlap with what follows
