@@ -4,8 +4,11 @@
 #include <cmath>
 #include <cstring>
 #include <numeric>
+#include <thread>
 #include <utility>
 #include <vector>
+
+#include <sched.h>
 
 #include "gnn_internal.h"
 
@@ -14,6 +17,44 @@ namespace gnn {
 static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(int e) { g_last_hip_error = e; }
 
+// Worker threads for the row-parallel passes: the cores this process may run on, at most 16, and
+// one per 256k entries so that small graphs stay on the calling thread.
+static int host_threads(int64_t nnz)
+{
+    cpu_set_t set;
+    int cores = 1;
+    if (sched_getaffinity(0, sizeof(set), &set) == 0) cores = CPU_COUNT(&set);
+    if (cores > 16) cores = 16;
+    const int64_t by_work = nnz / (256 * 1024) + 1;
+    if ((int64_t)cores > by_work) cores = (int)by_work;
+    return cores < 1 ? 1 : cores;
+}
+
+// Runs fn(row_begin, row_end, part) over contiguous row ranges that hold about the same number of
+// entries each (rowptr must be non-decreasing).  The results of the parts do not depend on how
+// many there are: every caller writes disjoint outputs or adds integers.
+template <typename F>
+static void for_row_ranges(int32_t n, const int32_t *rowptr, int parts, F fn)
+{
+    if (parts <= 1 || n <= 1) {
+        fn((int32_t)0, n, 0);
+        return;
+    }
+    std::vector<int32_t> cut((size_t)parts + 1, n);
+    cut[0] = 0;
+    const int64_t nnz = rowptr[n];
+    for (int t = 1; t < parts; ++t) {
+        const int64_t target = nnz * t / parts;
+        cut[t] = (int32_t)(std::lower_bound(rowptr, rowptr + n, (int32_t)target) - rowptr);
+        if (cut[t] < cut[t - 1]) cut[t] = cut[t - 1];
+    }
+    std::vector<std::thread> th;
+    th.reserve((size_t)parts - 1);
+    for (int t = 1; t < parts; ++t) th.emplace_back([&, t] { fn(cut[t], cut[t + 1], t); });
+    fn(cut[0], cut[1], 0);
+    for (auto &x : th) x.join();
+}
+
 static int check_host_csr(int32_t n, const int32_t *rowptr, const int32_t *colidx)
 {
     if (n < 0 || !rowptr) return GNN_EINVAL;
@@ -21,17 +62,30 @@ static int check_host_csr(int32_t n, const int32_t *rowptr, const int32_t *colid
     for (int32_t i = 0; i < n; ++i)
         if (rowptr[i + 1] < rowptr[i]) return GNN_ECSR;
     if (rowptr[n] > 0 && !colidx) return GNN_EINVAL;
-    const int64_t nnz = rowptr[n];
-    for (int64_t e = 0; e < nnz; ++e)
-        if (colidx[e] < 0 || colidx[e] >= n) return GNN_ECSR;
+    const int parts = host_threads(rowptr[n]);
+    std::vector<int> bad((size_t)parts, 0);
+    for_row_ranges(n, rowptr, parts, [&](int32_t lo, int32_t hi, int t) {
+        int b = 0;
+        for (int64_t e = rowptr[lo]; e < rowptr[hi]; ++e) b |= (colidx[e] < 0 || colidx[e] >= n);
+        bad[t] = b;
+    });
+    for (int b : bad)
+        if (b) return GNN_ECSR;
     return GNN_OK;
 }
 
 static int64_t aes_sum_host(int32_t n, const int32_t *rowptr, const int32_t *colidx)
 {
+    const int parts = host_threads(rowptr[n]);
+    std::vector<int64_t> part((size_t)parts, 0);
+    for_row_ranges(n, rowptr, parts, [&](int32_t lo, int32_t hi, int t) {
+        int64_t s = 0;
+        for (int32_t i = lo; i < hi; ++i)
+            for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) s += std::llabs((long long)i - (long long)colidx[e]);
+        part[t] = s;
+    });
     int64_t s = 0;
-    for (int32_t i = 0; i < n; ++i)
-        for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) s += std::llabs((long long)i - (long long)colidx[e]);
+    for (int64_t x : part) s += x;
     return s;
 }
 
@@ -244,14 +298,16 @@ int gnn_gcn_norm(int32_t n, const int32_t *rowptr, const int32_t *colidx, float 
     const int rc = check_host_csr(n, rowptr, colidx);
     if (rc != GNN_OK) return rc;
     if (rowptr[n] > 0 && !ew) return GNN_EINVAL;
-    for (int32_t i = 0; i < n; ++i) {
-        const double di = (double)(rowptr[i + 1] - rowptr[i]);
-        for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
-            const int32_t j = colidx[e];
-            const double dj = (double)(rowptr[j + 1] - rowptr[j]);
-            ew[e] = (float)(1.0 / std::sqrt(di * dj));
+    for_row_ranges(n, rowptr, host_threads(rowptr[n]), [&](int32_t lo, int32_t hi, int) {
+        for (int32_t i = lo; i < hi; ++i) {
+            const double di = (double)(rowptr[i + 1] - rowptr[i]);
+            for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+                const int32_t j = colidx[e];
+                const double dj = (double)(rowptr[j + 1] - rowptr[j]);
+                ew[e] = (float)(1.0 / std::sqrt(di * dj));
+            }
         }
-    }
+    });
     return GNN_OK;
 }
 
@@ -269,18 +325,21 @@ int gnn_apply_perm_csr(int32_t n, const int32_t *rowptr, const int32_t *colidx, 
     }
     rowptr2[0] = 0;
     for (int32_t r = 0; r < n; ++r) rowptr2[r + 1] = rowptr2[r] + (rowptr[inv[r] + 1] - rowptr[inv[r]]);
-    std::vector<std::pair<int32_t, int32_t>> row;  // (new column, position in the old row)
-    for (int32_t r = 0; r < n; ++r) {
-        const int32_t i = inv[r];
-        const int32_t len = rowptr[i + 1] - rowptr[i];
-        row.resize((size_t)len);
-        for (int32_t k = 0; k < len; ++k) row[k] = {perm[colidx[rowptr[i] + k]], k};
-        std::sort(row.begin(), row.end());
-        for (int32_t k = 0; k < len; ++k) {
-            colidx2[rowptr2[r] + k] = row[k].first;
-            if (val) val2[rowptr2[r] + k] = val[rowptr[i] + row[k].second];
+    // the new rows are independent of each other: ranges of them go to the worker threads
+    for_row_ranges(n, rowptr2, host_threads(rowptr[n]), [&](int32_t lo, int32_t hi, int) {
+        std::vector<std::pair<int32_t, int32_t>> row;  // (new column, position in the old row)
+        for (int32_t r = lo; r < hi; ++r) {
+            const int32_t i = inv[r];
+            const int32_t len = rowptr[i + 1] - rowptr[i];
+            row.resize((size_t)len);
+            for (int32_t k = 0; k < len; ++k) row[k] = {perm[colidx[rowptr[i] + k]], k};
+            std::sort(row.begin(), row.end());
+            for (int32_t k = 0; k < len; ++k) {
+                colidx2[rowptr2[r] + k] = row[k].first;
+                if (val) val2[rowptr2[r] + k] = val[rowptr[i] + row[k].second];
+            }
         }
-    }
+    });
     return GNN_OK;
 }
 

@@ -37,7 +37,8 @@ static void random_symmetric(int n, int m, unsigned seed, bool loops, std::vecto
 
 int main()
 {
-    const int shapes[][2] = {{0, 0}, {1, 0}, {1, 3}, {2, 1}, {17, 40}, {300, 900}, {2000, 30000}, {5000, 6000}};
+    const int shapes[][2] = {{0, 0}, {1, 0}, {1, 3}, {2, 1}, {17, 40}, {300, 900}, {2000, 30000}, {5000, 6000},
+                             {40000, 450000} /* large enough for the worker threads of the row-parallel passes */};
     unsigned seed = 1;
     for (const auto &sh : shapes) {
         for (int loops = 0; loops < 2; ++loops) {
