@@ -13,6 +13,8 @@ from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
+from .parallel_reorder import parallel_reorder  # noqa: F401  (round-based renumbering, numpy)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gnn_oracle.c")
 _LIB = os.path.join(_HERE, "libgnn_oracle.so")
