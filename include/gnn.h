@@ -15,7 +15,8 @@
  *   - "HOST" / "DEVICE" on a pointer says where the memory must live.  The caller owns
  *     every buffer and the library keeps no state between calls.  The compute entry points
  *     allocate nothing; only the diagnostic calls that copy results to the host
- *     (gnn_block_layout_export, gnn_validate_csr_device) use a temporary device buffer.
+ *     (gnn_block_layout_export, gnn_validate_csr_device) and the one-time graph preparation on
+ *     the device (gnn_reorder_device, gnn_apply_perm_csr_device) use temporary device buffers.
  *   - Matrices are row-major fp32; CSR indices are int32 (nnz < 2^31); n * dim is
  *     addressed in 64 bits.  In and out buffers must not alias.
  *   - DEVICE entry points only enqueue work on `stream` (a hipStream_t, NULL = the null
@@ -271,6 +272,30 @@ int gnn_layer_backward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr_t
                        int32_t out_dim, int relu, const float *Y, const float *dY, float *dX, float *dW,
                        float *db, int32_t ngs, int32_t dw, int32_t waves_per_block, uint32_t flags,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Graph preparation on the DEVICE (one-time per graph; these three allocate their own temporaries
+ * with hipMalloc and, except gnn_gcn_norm_device, synchronise `stream` before they return).
+ *
+ * gnn_reorder_device: the community renumbering of Sec. 5.1 with a round-based merge schedule (all
+ * communities act on the same state in synchronous rounds: propose to the neighbouring community of
+ * largest modularity gain, the smaller id of a mutual pair stays, only proposals to a community that
+ * does not move itself are carried out, joiners are appended by ascending id; new ids = communities
+ * by ascending root id, then position).  The permutation differs from gnn_reorder's (another merge
+ * schedule) and gives about the same locality at a small fraction of the time.  DEVICE rowptr[n+1],
+ * colidx[nnz] (symmetric CSR, validated), DEVICE perm[n], iperm[n].  max_rounds bounds the rounds (64
+ * is ample); rounds_out (HOST, may be NULL) receives the rounds that merged something.  No AES rule
+ * here: call gnn_aes / decide on the host if wanted.  Deterministic (integer arithmetic only).
+ * Errors: GNN_EINVAL, GNN_ECSR (column index out of range), GNN_EHIP.
+ *
+ * gnn_apply_perm_csr_device: gnn_apply_perm_csr on DEVICE arrays, same result byte for byte.
+ * Errors: GNN_EINVAL (perm not a bijection), GNN_ECSR, GNN_EHIP.
+ *
+ * gnn_gcn_norm_device: gnn_gcn_norm on DEVICE arrays, same result byte for byte; only enqueues. */
+int gnn_reorder_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, int32_t *perm,
+                       int32_t *iperm, int32_t max_rounds, int32_t *rounds_out, void *stream);
+int gnn_apply_perm_csr_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                              const int32_t *perm, int32_t *rowptr2, int32_t *colidx2, float *val2, void *stream);
+int gnn_gcn_norm_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, float *ew, void *stream);
 
 /* Row gather for renumbering: Y[perm[i],:] = X[i,:] (pass iperm to undo).  DEVICE pointers,
  * perm int32[n]. */

@@ -12,6 +12,7 @@ __all__ = [
     "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_XCD_RUNS", "GNN_FLAG_NO_PIPELINE",
     "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_FLAG_NO_FUSION", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
     "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall", "AggregateCall",
+    "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
@@ -40,6 +41,7 @@ _SYMBOLS = [
     "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward",
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
     "gnn_last_hip_error", "gnn_version", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
+    "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device",
 ]
 
 
@@ -419,3 +421,42 @@ def gnn_permute_rows(n, dim, perm, X, Y, stream=None):
     rc = load().gnn_permute_rows(_i32(n), _i32(dim), _dev(perm, "int32", "perm"), _dev(X, "float32", "X"),
                                  _dev(Y, "float32", "Y"), _stream(stream))
     _check(rc, "gnn_permute_rows")
+
+
+# ------------------------------------------------------------------ graph preparation on the device
+def gnn_reorder_device(n, nnz, rowptr, colidx, max_rounds: int = 64, stream=None):
+    """Round-based community renumbering on DEVICE int32 tensors.  Returns (perm, iperm, rounds)."""
+    import torch
+    perm = torch.empty(max(int(n), 1), dtype=torch.int32, device=rowptr.device)[: int(n)]
+    iperm = torch.empty(max(int(n), 1), dtype=torch.int32, device=rowptr.device)[: int(n)]
+    rounds = ctypes.c_int32(0)
+    rc = load().gnn_reorder_device(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"), _dev(colidx, "int32", "colidx"),
+                                   _dev(perm, "int32", "perm"), _dev(iperm, "int32", "iperm"), _i32(max_rounds),
+                                   ctypes.byref(rounds), _stream(stream))
+    _check(rc, "gnn_reorder_device")
+    return perm, iperm, int(rounds.value)
+
+
+def gnn_apply_perm_csr_device(n, nnz, rowptr, colidx, perm, val=None, stream=None):
+    """gnn_apply_perm_csr on DEVICE tensors.  Returns (rowptr2, colidx2) or (rowptr2, colidx2, val2)."""
+    import torch
+    rowptr2 = torch.empty(int(n) + 1, dtype=torch.int32, device=rowptr.device)
+    colidx2 = torch.empty(max(int(nnz), 1), dtype=torch.int32, device=rowptr.device)[: int(nnz)]
+    val2 = None if val is None else torch.empty(max(int(nnz), 1), dtype=torch.float32, device=rowptr.device)[: int(nnz)]
+    rc = load().gnn_apply_perm_csr_device(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"),
+                                          _dev(colidx, "int32", "colidx"), _dev(val, "float32", "val"),
+                                          _dev(perm, "int32", "perm"), _dev(rowptr2, "int32", "rowptr2"),
+                                          _dev(colidx2, "int32", "colidx2"), _dev(val2, "float32", "val2"),
+                                          _stream(stream))
+    _check(rc, "gnn_apply_perm_csr_device")
+    return (rowptr2, colidx2) if val is None else (rowptr2, colidx2, val2)
+
+
+def gnn_gcn_norm_device(n, nnz, rowptr, colidx, stream=None):
+    """Eq. 2 weights on DEVICE tensors; returns the float32 tensor ew[nnz] (work is only enqueued)."""
+    import torch
+    ew = torch.empty(max(int(nnz), 1), dtype=torch.float32, device=rowptr.device)[: int(nnz)]
+    rc = load().gnn_gcn_norm_device(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"), _dev(colidx, "int32", "colidx"),
+                                    _dev(ew, "float32", "ew"), _stream(stream))
+    _check(rc, "gnn_gcn_norm_device")
+    return ew
