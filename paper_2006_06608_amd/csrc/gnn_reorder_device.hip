@@ -64,17 +64,32 @@ __global__ void k_edge_keys(int n, int64_t nnz, const int *__restrict__ rowptr, 
         const bool outside = j < 0 || j >= n;  // malformed CSR: reported, the entry is dropped
         const bool loop = i == j || outside;
         key[e] = loop ? make_key((uint32_t)n, 0u) : make_key((uint32_t)i, (uint32_t)j);
-        if (loop) atomicAdd(&counters[0], 1);
-        if (outside) atomicAdd(&counters[3], 1);
+        // flags, not counts: millions of atomics on one address would serialise
+        if (loop) counters[0] = 1;
+        if (outside) counters[3] = 1;
     }
 }
 
 __global__ void k_fill_i32(int *__restrict__ a, int64_t count, int value) { GRID_STRIDE(i, count) a[i] = value; }
 __global__ void k_iota_i32(int *__restrict__ a, int64_t count) { GRID_STRIDE(i, count) a[i] = (int)i; }
 
-__global__ void k_degrees(const uint64_t *__restrict__ key, int64_t m, int *__restrict__ degw)
+// clean degree of every node = length of its run in the sorted key list (no atomics: hubs would
+// serialise them).  First the run heads note where they start, then the run tails write the length.
+__global__ void k_degree_heads(const uint64_t *__restrict__ key, int64_t m, int *__restrict__ run_start)
 {
-    GRID_STRIDE(e, m) atomicAdd(&degw[(int)(key[e] >> 32)], 1);
+    GRID_STRIDE(e, m) {
+        const int cu = (int)(key[e] >> 32);
+        if (e == 0 || (int)(key[e - 1] >> 32) != cu) run_start[cu] = (int)e;
+    }
+}
+
+__global__ void k_degree_tails(const uint64_t *__restrict__ key, int64_t m, const int *__restrict__ run_start,
+                               int *__restrict__ degw)
+{
+    GRID_STRIDE(e, m) {
+        const int cu = (int)(key[e] >> 32);
+        if (e == m - 1 || (int)(key[e + 1] >> 32) != cu) degw[cu] = (int)e + 1 - run_start[cu];
+    }
 }
 
 // ---- one round ---------------------------------------------------------------------------------
@@ -98,7 +113,24 @@ __device__ __forceinline__ long long edge_score(uint64_t k, int w, long long M2,
 __global__ void k_score_max(const uint64_t *__restrict__ key, const int *__restrict__ w, int64_t m, long long M2,
                             const int *__restrict__ degw, long long *__restrict__ bestS)
 {
-    GRID_STRIDE(e, m) atomicMax(&bestS[(int)(key[e] >> 32)], edge_score(key[e], w[e], M2, degw));
+    // The keys are sorted, so the edges of one community are neighbours: the lanes of a wave first
+    // combine the scores of equal communities among themselves (segmented max scan over the wave),
+    // and only the last lane of every run goes to memory -- a hub's 10^4 edges cost 10^2 atomics.
+    const int lane = threadIdx.x & 63;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t base = (int64_t)blockIdx.x * blockDim.x + threadIdx.x - lane; base < m; base += stride) {
+        const int64_t e = base + lane;
+        const bool live = e < m;
+        const int cu = live ? (int)(key[e] >> 32) : -1;
+        long long sc = live ? edge_score(key[e], w[e], M2, degw) : LLONG_MIN;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int ocu = __shfl_up(cu, o);
+            const long long osc = __shfl_up(sc, o);
+            if (lane >= o && ocu == cu && osc > sc) sc = osc;
+        }
+        const int ncu = __shfl_down(cu, 1);
+        if (live && (lane == 63 || ncu != cu)) atomicMax(&bestS[cu], sc);
+    }
 }
 
 __global__ void k_score_arg(const uint64_t *__restrict__ key, const int *__restrict__ w, int64_t m, long long M2,
@@ -133,7 +165,10 @@ __global__ void k_stars(int n, const int *__restrict__ prop, const int *__restri
         target[u] = joins ? p : (int)u;
         jkey[u] = joins ? make_key((uint32_t)p, (uint32_t)u) : make_key((uint32_t)n, 0u);
         jsize[u] = joins ? size[u] : 0;
-        if (joins) atomicAdd(&counters[1], 1);
+        // number of joiners: one atomic per wave
+        const unsigned long long votes = __ballot(joins);
+        if (votes != 0ull && (threadIdx.x & 63) == (unsigned)(__ffsll((long long)votes) - 1))
+            atomicAdd(&counters[1], __popcll(votes));
     }
 }
 
@@ -182,7 +217,7 @@ __global__ void k_rename_edges(int n, uint64_t *__restrict__ key, int64_t m, con
         const int cu = target[(int)(key[e] >> 32)], cv = target[(int)(uint32_t)key[e]];
         const bool inner = cu == cv;
         key[e] = inner ? make_key((uint32_t)n, 0u) : make_key((uint32_t)cu, (uint32_t)cv);
-        if (inner) atomicAdd(&counters[2], 1);
+        if (inner) counters[2] = 1;  // a flag: some edge fell inside a community
     }
 }
 
@@ -387,7 +422,8 @@ int gnn_reorder_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int3
         m = (int64_t)host_runs - (host_counters[0] > 0 ? 1 : 0);  // the self loops collapsed into one last key
         if (m > 0) {
             hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(m)), dim3(kThreads), 0, s, wA, m, 1);
-            hipLaunchKernelGGL(k_degrees, dim3(blocks_for(m)), dim3(kThreads), 0, s, keyA, m, degw);
+            hipLaunchKernelGGL(k_degree_heads, dim3(blocks_for(m)), dim3(kThreads), 0, s, keyA, m, head);
+            hipLaunchKernelGGL(k_degree_tails, dim3(blocks_for(m)), dim3(kThreads), 0, s, keyA, m, head, degw);
         }
     }
     const long long M2 = (long long)m;
