@@ -291,24 +291,36 @@ __global__ void k_gcn_norm(int n, int64_t nnz, const int *__restrict__ rowptr, c
     }
 }
 
-// Device temporaries of one call, released when it returns.
+// Device temporaries of one call: sizes are registered first, then one allocation serves them all
+// (two dozen separate allocations cost more than the kernels of a renumbering), released on return.
 struct Arena {
-    std::vector<void *> ptrs;
+    struct Slot {
+        void **out;
+        size_t offset;
+    };
+    std::vector<Slot> slots;
+    size_t total = 0;
+    char *base = nullptr;
     ~Arena()
     {
-        for (void *p : ptrs) (void)hipFree(p);
+        if (base) (void)hipFree(base);
     }
     template <typename T>
-    int get(T **out, size_t count)
+    void want(T **out, size_t count)
+    {
+        slots.push_back({reinterpret_cast<void **>(out), total});
+        total += align_up((count > 0 ? count : 1) * sizeof(T));
+    }
+    int commit()
     {
         void *p = nullptr;
-        const hipError_t e = hipMalloc(&p, (count > 0 ? count : 1) * sizeof(T));
+        const hipError_t e = hipMalloc(&p, total > 0 ? total : kAlign);
         if (e != hipSuccess) {
             set_last_hip_error((int)e);
             return GNN_EHIP;
         }
-        ptrs.push_back(p);
-        *out = (T *)p;
+        base = (char *)p;
+        for (const Slot &sl : slots) *sl.out = base + sl.offset;
         return GNN_OK;
     }
 };
@@ -352,52 +364,56 @@ int gnn_reorder_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int3
     int *wA, *wB, *jsA, *jsB, *comm, *pos, *size, *degw, *bestv, *best, *prop, *target, *shift, *before, *head, *start;
     int *counters, *nruns;
     long long *bestS;
-    GNN_TRY(mem.get(&keyA, (size_t)nnz));
-    GNN_TRY(mem.get(&keyB, (size_t)nnz));
-    GNN_TRY(mem.get(&wA, (size_t)nnz));
-    GNN_TRY(mem.get(&wB, (size_t)nnz));
-    GNN_TRY(mem.get(&jkeyA, (size_t)n));
-    GNN_TRY(mem.get(&jkeyB, (size_t)n));
-    GNN_TRY(mem.get(&jsA, (size_t)n));
-    GNN_TRY(mem.get(&jsB, (size_t)n));
-    GNN_TRY(mem.get(&comm, (size_t)n));
-    GNN_TRY(mem.get(&pos, (size_t)n));
-    GNN_TRY(mem.get(&size, (size_t)n));
-    GNN_TRY(mem.get(&degw, (size_t)n));
-    GNN_TRY(mem.get(&bestv, (size_t)n));
-    GNN_TRY(mem.get(&best, (size_t)n));
-    GNN_TRY(mem.get(&prop, (size_t)n));
-    GNN_TRY(mem.get(&target, (size_t)n));
-    GNN_TRY(mem.get(&shift, (size_t)n));
-    GNN_TRY(mem.get(&before, (size_t)n));
-    GNN_TRY(mem.get(&head, (size_t)n));
-    GNN_TRY(mem.get(&start, (size_t)n));
-    GNN_TRY(mem.get(&bestS, (size_t)n));
-    GNN_TRY(mem.get(&counters, 4));
-    GNN_TRY(mem.get(&nruns, 1));
+    mem.want(&keyA, (size_t)nnz);
+    mem.want(&keyB, (size_t)nnz);
+    mem.want(&wA, (size_t)nnz);
+    mem.want(&wB, (size_t)nnz);
+    mem.want(&jkeyA, (size_t)n);
+    mem.want(&jkeyB, (size_t)n);
+    mem.want(&jsA, (size_t)n);
+    mem.want(&jsB, (size_t)n);
+    mem.want(&comm, (size_t)n);
+    mem.want(&pos, (size_t)n);
+    mem.want(&size, (size_t)n);
+    mem.want(&degw, (size_t)n);
+    mem.want(&bestv, (size_t)n);
+    mem.want(&best, (size_t)n);
+    mem.want(&prop, (size_t)n);
+    mem.want(&target, (size_t)n);
+    mem.want(&shift, (size_t)n);
+    mem.want(&before, (size_t)n);
+    mem.want(&head, (size_t)n);
+    mem.want(&start, (size_t)n);
+    mem.want(&bestS, (size_t)n);
+    mem.want(&counters, 4);
+    mem.want(&nruns, 1);
 
-    // temporary storage of the library primitives: the largest any call below asks for
+    // temporary storage of the library primitives: the largest any call below asks for (a size query
+    // only looks at the types of its pointer arguments)
     size_t tmp_bytes = 0;
     {
         size_t b = 0;
         const int mm = (int)nnz;
-        GNN_HIP_TRY(hipcub::DeviceRadixSort::SortKeys(nullptr, b, keyA, keyB, mm, 0, key_bits, s));
+        uint64_t *k0 = nullptr, *k1 = nullptr;
+        int *v0 = nullptr, *v1 = nullptr, *cnt = nullptr;
+        GNN_HIP_TRY(hipcub::DeviceRadixSort::SortKeys(nullptr, b, k0, k1, mm, 0, key_bits, s));
         tmp_bytes = b > tmp_bytes ? b : tmp_bytes;
-        GNN_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(nullptr, b, keyA, keyB, wA, wB, mm, 0, key_bits, s));
+        GNN_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(nullptr, b, k0, k1, v0, v1, mm, 0, key_bits, s));
         tmp_bytes = b > tmp_bytes ? b : tmp_bytes;
-        GNN_HIP_TRY(hipcub::DeviceSelect::Unique(nullptr, b, keyB, keyA, nruns, mm, s));
+        GNN_HIP_TRY(hipcub::DeviceSelect::Unique(nullptr, b, k0, k1, cnt, mm, s));
         tmp_bytes = b > tmp_bytes ? b : tmp_bytes;
-        GNN_HIP_TRY(hipcub::DeviceReduce::ReduceByKey(nullptr, b, keyB, keyA, wB, wA, nruns, hipcub::Sum(), mm, s));
+        GNN_HIP_TRY(hipcub::DeviceReduce::ReduceByKey(nullptr, b, k0, k1, v0, v1, cnt, hipcub::Sum(), mm, s));
         tmp_bytes = b > tmp_bytes ? b : tmp_bytes;
-        GNN_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(nullptr, b, jkeyA, jkeyB, jsA, jsB, n, 0, key_bits, s));
+        GNN_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(nullptr, b, k0, k1, v0, v1, n, 0, key_bits, s));
         tmp_bytes = b > tmp_bytes ? b : tmp_bytes;
-        GNN_HIP_TRY(hipcub::DeviceScan::ExclusiveSum(nullptr, b, jsB, before, n, s));
+        GNN_HIP_TRY(hipcub::DeviceScan::ExclusiveSum(nullptr, b, v0, v1, n, s));
         tmp_bytes = b > tmp_bytes ? b : tmp_bytes;
-        GNN_HIP_TRY(hipcub::DeviceScan::InclusiveScan(nullptr, b, head, start, hipcub::Max(), n, s));
+        GNN_HIP_TRY(hipcub::DeviceScan::InclusiveScan(nullptr, b, v0, v1, hipcub::Max(), n, s));
         tmp_bytes = b > tmp_bytes ? b : tmp_bytes;
     }
     char *tmp;
-    GNN_TRY(mem.get(&tmp, tmp_bytes));
+    mem.want(&tmp, tmp_bytes);
+    GNN_TRY(mem.commit());
 
     int host_counters[4] = {0, 0, 0, 0};
     int host_runs = 0;
@@ -489,21 +505,26 @@ int gnn_apply_perm_csr_device(int32_t n, int64_t nnz, const int32_t *rowptr, con
     Arena mem;
     uint64_t *keyA, *keyB;
     int *entA, *entB, *len2, *seen, *bad;
-    GNN_TRY(mem.get(&keyA, (size_t)nnz));
-    GNN_TRY(mem.get(&keyB, (size_t)nnz));
-    GNN_TRY(mem.get(&entA, (size_t)nnz));
-    GNN_TRY(mem.get(&entB, (size_t)nnz));
-    GNN_TRY(mem.get(&len2, (size_t)n + 1));
-    GNN_TRY(mem.get(&seen, (size_t)n + 1));
-    GNN_TRY(mem.get(&bad, 1));
+    mem.want(&keyA, (size_t)nnz);
+    mem.want(&keyB, (size_t)nnz);
+    mem.want(&entA, (size_t)nnz);
+    mem.want(&entB, (size_t)nnz);
+    mem.want(&len2, (size_t)n + 1);
+    mem.want(&seen, (size_t)n + 1);
+    mem.want(&bad, 1);
     const int key_bits = 32 + bit_length((uint32_t)n);
     size_t tmp_bytes = 0, b = 0;
-    GNN_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(nullptr, b, keyA, keyB, entA, entB, (int)nnz, 0, key_bits, s));
-    tmp_bytes = b;
-    GNN_HIP_TRY(hipcub::DeviceScan::ExclusiveSum(nullptr, b, len2, rowptr2, n + 1, s));
-    tmp_bytes = b > tmp_bytes ? b : tmp_bytes;
+    {
+        uint64_t *k0 = nullptr, *k1 = nullptr;
+        int *v0 = nullptr, *v1 = nullptr;
+        GNN_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(nullptr, b, k0, k1, v0, v1, (int)nnz, 0, key_bits, s));
+        tmp_bytes = b;
+        GNN_HIP_TRY(hipcub::DeviceScan::ExclusiveSum(nullptr, b, v0, v1, n + 1, s));
+        tmp_bytes = b > tmp_bytes ? b : tmp_bytes;
+    }
     char *tmp;
-    GNN_TRY(mem.get(&tmp, tmp_bytes));
+    mem.want(&tmp, tmp_bytes);
+    GNN_TRY(mem.commit());
 
     // perm must be a bijection of [0, n)
     hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(n + 1)), dim3(kThreads), 0, s, seen, (int64_t)n + 1, 0);
