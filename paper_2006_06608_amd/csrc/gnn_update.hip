@@ -17,6 +17,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kGemmRows = 64;        // rows of A per tile (4 waves x 16)
 constexpr int kGemmKC = 32;          // K chunk staged per step
 constexpr int kGemmWFloats = 12288;  // LDS floats available for the W slice (48 KB)
+constexpr int kGemmKsplitRows = 32768;  // up to here 16-row tiles whose waves split K (k_update_gemm_ksplit)
 constexpr int kGemmFewRows = 65536;  // below this many rows every block of the grid gets at most one 64-row tile
 
 struct GemmParams {
@@ -321,6 +322,145 @@ __global__ __launch_bounds__(256) void k_update_gemm_few(GemmParams p)
     }
 }
 
+// Very few rows (n <= 32,768) and K >= 256: 64-row tiles give fewer blocks than the chip has CUs, so
+// the tile shrinks to 16 rows and the four waves of a block split every K chunk among themselves
+// (each multiplies the same 16 rows by its quarter of the chunk); their partial products are added
+// through LDS at the end.  Four times the blocks of k_update_gemm_few, the same bytes per block and
+// chunk in flight.
+template <int MT, bool VEC4, bool WV4, int KC>
+__global__ __launch_bounds__(256) void k_update_gemm_ksplit(GemmParams p)
+{
+    extern __shared__ __align__(16) float smem_f[];
+    constexpr int MP = 16 * MT, LDW = MP + 4, LDA = KC + 4, NT = 256;
+    constexpr int F4 = 16 * KC / 4 / NT, F1 = 16 * KC / NT;
+    constexpr int MQ = MP / 4, W4 = KC * MQ / NT, W1 = KC * MP / NT;
+    constexpr int KW = KC / 4;  // K range of one wave inside a chunk
+    static_assert((16 * KC / 4) % NT == 0 && (KC * MQ) % NT == 0 && KW % 16 == 0, "chunk shape");
+    static_assert(4 * MT * 256 <= KC * LDW, "the partial products reuse the W chunk's LDS");
+    float *s_W = smem_f;             // [KC][LDW]; afterwards [4][MT][256] partial products
+    float *s_A = smem_f + KC * LDW;  // [16][LDA]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col0 = blockIdx.y * MP;
+    const int lrow = lane & 15, lk = lane >> 4;
+    const int64_t row0 = (int64_t)blockIdx.x * 16;
+    const int kpad = (p.K + KC - 1) / KC * KC;
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    float4 a4r[VEC4 ? F4 : 1], w4r[WV4 ? W4 : 1];
+    float a1r[VEC4 ? 1 : F1], w1r[WV4 ? 1 : W1];
+    auto fetch = [&](int kc) {
+        if constexpr (VEC4) {
+#pragma unroll
+            for (int i = 0; i < F4; ++i) {
+                const int e = tid + NT * i;
+                const int64_t row = row0 + e / (KC / 4);
+                const int k = kc + (e % (KC / 4)) * 4;
+                a4r[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (row < p.n && k < p.K) a4r[i] = *reinterpret_cast<const float4 *>(p.A + (size_t)row * p.K + k);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < F1; ++i) {
+                const int e = tid + NT * i;
+                const int64_t row = row0 + e / KC;
+                const int k = kc + e % KC;
+                a1r[i] = (row < p.n && k < p.K) ? p.A[(size_t)row * p.K + k] : 0.0f;
+            }
+        }
+        if constexpr (WV4) {
+#pragma unroll
+            for (int j = 0; j < W4; ++j) {
+                const int i = tid + NT * j;
+                const int k = kc + i / MQ, c = col0 + (i % MQ) * 4;
+                w4r[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (k < p.K && c < p.M) w4r[j] = *reinterpret_cast<const float4 *>(p.W + (size_t)k * p.M + c);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < W1; ++j) {
+                const int i = tid + NT * j;
+                const int k = kc + i / MP, c = col0 + i % MP;
+                w1r[j] = (k < p.K && c < p.M) ? p.W[(size_t)k * p.M + c] : 0.0f;
+            }
+        }
+    };
+    auto commit = [&]() {
+        if constexpr (VEC4) {
+#pragma unroll
+            for (int i = 0; i < F4; ++i) {
+                const int e = tid + NT * i;
+                *reinterpret_cast<float4 *>(&s_A[(e / (KC / 4)) * LDA + (e % (KC / 4)) * 4]) = a4r[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < F1; ++i) {
+                const int e = tid + NT * i;
+                s_A[(e / KC) * LDA + e % KC] = a1r[i];
+            }
+        }
+        if constexpr (WV4) {
+#pragma unroll
+            for (int j = 0; j < W4; ++j) {
+                const int i = tid + NT * j;
+                *reinterpret_cast<float4 *>(&s_W[(i / MQ) * LDW + (i % MQ) * 4]) = w4r[j];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < W1; ++j) {
+                const int i = tid + NT * j;
+                s_W[(i / MP) * LDW + i % MP] = w1r[j];
+            }
+        }
+    };
+
+    fetch(0);
+    for (int kc = 0; kc < kpad; kc += KC) {
+        __syncthreads();  // previous chunk fully consumed
+        commit();
+        __syncthreads();
+        if (kc + KC < kpad) fetch(kc + KC);
+        const float *arow = &s_A[lrow * LDA + wave * KW];
+#pragma unroll
+        for (int ks = 0; ks < KW; ks += 16) {
+            const float4 a4 = *reinterpret_cast<const float4 *>(arow + ks + 4 * lk);
+            const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+            const float *wrow = &s_W[(wave * KW + ks + 4 * lk) * LDW + lrow];
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s4], wrow[s4 * LDW + t * 16], acc[t], 0, 0, 0);
+            }
+        }
+    }
+
+    // add the four waves' partial products: lane holds rows 4*lk+i, column lrow of each 16x16 tile
+    __syncthreads();  // the W chunk is no longer read
+    float *s_red = s_W;
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s_red[(wave * MT + t) * 256 + (4 * lk + i) * 16 + lrow] = acc[t][i];
+    __syncthreads();
+    const int r = tid >> 4, c16 = tid & 15;
+    const int64_t row = row0 + r;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const int col = col0 + t * 16 + c16;
+        float v = (s_red[(0 * MT + t) * 256 + tid] + s_red[(1 * MT + t) * 256 + tid]) +
+                  (s_red[(2 * MT + t) * 256 + tid] + s_red[(3 * MT + t) * 256 + tid]);
+        if (row < p.n && col < p.M) {
+            if (p.b) v += p.b[col];
+            if (p.relu) v = fmaxf(v, 0.0f);
+            p.out[(size_t)row * p.M + col] = v;
+        }
+    }
+}
+
 // Streaming form for K <= 32 (K a multiple of 4) and M <= 64, where staging through LDS costs more
 // than it saves (measured 15 us against 22 us for 410k x 16 x 22; no gain from K = 64 on): no LDS, no
 // barrier.  A wave owns 16-row tiles; its W fragments (all columns) stay in registers for the whole
@@ -408,6 +548,16 @@ static void launch_gemm(bool vec4, dim3 grid, size_t lds, hipStream_t s, const G
 }
 
 template <int MT, int KC>
+static void launch_gemm_ksplit(bool vec4, bool wv4, dim3 grid, hipStream_t s, const GemmParams &p)
+{
+    const size_t lds = ((size_t)KC * (16 * MT + 4) + (size_t)16 * (KC + 4)) * sizeof(float);
+    if (vec4 && wv4) hipLaunchKernelGGL((k_update_gemm_ksplit<MT, true, true, KC>), grid, dim3(256), lds, s, p);
+    else if (vec4) hipLaunchKernelGGL((k_update_gemm_ksplit<MT, true, false, KC>), grid, dim3(256), lds, s, p);
+    else if (wv4) hipLaunchKernelGGL((k_update_gemm_ksplit<MT, false, true, KC>), grid, dim3(256), lds, s, p);
+    else hipLaunchKernelGGL((k_update_gemm_ksplit<MT, false, false, KC>), grid, dim3(256), lds, s, p);
+}
+
+template <int MT, int KC>
 static void launch_gemm_few(bool vec4, bool wv4, dim3 grid, hipStream_t s, const GemmParams &p)
 {
     const size_t lds = ((size_t)KC * (16 * MT + 4) + (size_t)64 * (KC + 4)) * sizeof(float);
@@ -450,6 +600,14 @@ int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const floa
         p.k_begin = 0; p.k_end = K; p.accumulate = 0; p.finish = 1;
         p.relu = relu;
         const bool wv4 = (M % 4 == 0) && ((uintptr_t)W % 16 == 0);
+        if (n <= kGemmKsplitRows && K >= 256) {  // too few 64-row tiles for the chip: 16-row tiles, waves split K
+            const dim3 grid16((unsigned)(((int64_t)n + 15) / 16), (unsigned)((M + MP - 1) / MP));
+            if (MT == 1) launch_gemm_ksplit<1, 256>(vec4, wv4, grid16, s, p);
+            else if (MT == 2) launch_gemm_ksplit<2, 256>(vec4, wv4, grid16, s, p);
+            else launch_gemm_ksplit<4, 128>(vec4, wv4, grid16, s, p);
+            GNN_HIP_TRY(hipGetLastError());
+            return GNN_OK;
+        }
         const dim3 grid((unsigned)ntiles, (unsigned)((M + MP - 1) / MP));
         if (MT == 1) launch_gemm_few<1, 128>(vec4, wv4, grid, s, p);
         else if (MT == 2) launch_gemm_few<2, 128>(vec4, wv4, grid, s, p);
