@@ -12,7 +12,7 @@ __all__ = [
     "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_XCD_RUNS", "GNN_FLAG_NO_PIPELINE",
     "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_FLAG_NO_FUSION", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
     "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall", "AggregateCall",
-    "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device",
+    "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
@@ -41,7 +41,7 @@ _SYMBOLS = [
     "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward",
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
     "gnn_last_hip_error", "gnn_version", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
-    "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device",
+    "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
 ]
 
 
@@ -460,3 +460,12 @@ def gnn_gcn_norm_device(n, nnz, rowptr, colidx, stream=None):
                                     _dev(ew, "float32", "ew"), _stream(stream))
     _check(rc, "gnn_gcn_norm_device")
     return ew
+
+
+def gnn_aes_device(n, nnz, rowptr, colidx, stream=None):
+    """Eq. 4 on DEVICE tensors.  Returns (aes_sum, aes, should_reorder)."""
+    total, mean, want = ctypes.c_int64(0), ctypes.c_double(0.0), ctypes.c_int(0)
+    rc = load().gnn_aes_device(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"), _dev(colidx, "int32", "colidx"),
+                               ctypes.byref(total), ctypes.byref(mean), ctypes.byref(want), _stream(stream))
+    _check(rc, "gnn_aes_device")
+    return int(total.value), float(mean.value), bool(want.value)

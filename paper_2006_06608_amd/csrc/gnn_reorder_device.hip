@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 #include <hipcub/hipcub.hpp>
 
+#include <cmath>
 #include <vector>
 
 #include "gnn_internal.h"
@@ -275,6 +276,19 @@ __global__ void k_perm_check(int n, const int *__restrict__ perm, int *__restric
         const int p = perm[i];
         if (p < 0 || p >= n || atomicAdd(&seen[p], 1) != 0) atomicAdd(bad, 1);
     }
+}
+
+// Eq. 4: sum over the stored entries of |row - column|, one atomic per wave.
+__global__ void k_aes_sum(int n, int64_t nnz, const int *__restrict__ rowptr, const int *__restrict__ colidx,
+                          unsigned long long *__restrict__ total)
+{
+    unsigned long long mine = 0;
+    GRID_STRIDE(e, nnz) {
+        const long long d = (long long)row_of(rowptr, n, e) - (long long)colidx[e];
+        mine += (unsigned long long)(d < 0 ? -d : d);
+    }
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_down(mine, o);
+    if ((threadIdx.x & 63) == 0 && mine != 0ull) atomicAdd(total, mine);
 }
 
 __global__ void k_gcn_norm(int n, int64_t nnz, const int *__restrict__ rowptr, const int *__restrict__ colidx,
@@ -551,6 +565,37 @@ int gnn_apply_perm_csr_device(int32_t n, int64_t nnz, const int32_t *rowptr, con
     }
     GNN_HIP_TRY(hipGetLastError());
     GNN_HIP_TRY(hipStreamSynchronize(s));
+    return GNN_OK;
+}
+
+int gnn_aes_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, int64_t *aes_sum, double *aes,
+                   int *should_reorder, void *stream)
+{
+    if (n < 0 || nnz < 0 || nnz >= ((int64_t)1 << 31)) return GNN_EINVAL;
+    if (nnz > 0 && (!rowptr || !colidx)) return GNN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    unsigned long long host_total = 0;
+    if (nnz > 0) {
+        Arena mem;
+        unsigned long long *total;
+        mem.want(&total, 1);
+        GNN_TRY(mem.commit());
+        hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(kThreads), 0, s, (int *)total, (int64_t)2, 0);
+        hipLaunchKernelGGL(k_aes_sum, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, n, nnz, rowptr, colidx, total);
+        GNN_HIP_TRY(hipGetLastError());
+        GNN_HIP_TRY(hipMemcpyAsync(&host_total, total, sizeof(host_total), hipMemcpyDeviceToHost, s));
+        GNN_HIP_TRY(hipStreamSynchronize(s));
+    }
+    if (aes_sum) *aes_sum = (int64_t)host_total;
+    if (aes) *aes = nnz > 0 ? (double)host_total / (double)nnz : 0.0;
+    if (should_reorder) {
+        // sqrt(AES) > floor(sqrt(n) / 100), compared in integers: sum > T^2 * nnz
+        long long r = (long long)sqrt((double)n);
+        while (r * r > (long long)n) --r;
+        while ((r + 1) * (r + 1) <= (long long)n) ++r;
+        const long long T = r / 100;
+        *should_reorder = (long long)host_total > T * T * (long long)nnz ? 1 : 0;
+    }
     return GNN_OK;
 }
 

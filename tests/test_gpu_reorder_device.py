@@ -99,6 +99,16 @@ def test_device_relabel_and_weights_equal_the_oracle_byte_for_byte(name):
     assert torch.equal(rp3, rp2) and torch.equal(ci3, ci2)
 
 
+@pytest.mark.parametrize("name", ["cfg1", "cfg3/8", "cfg4/16", "cfg5/16"])
+def test_device_aes_and_rule_equal_the_oracle(name):
+    g = dict(_graphs())[name]
+    rpd, cid = _dev_csr(g.rowptr, g.colidx)
+    total, mean, want = gnn.gnn_aes_device(g.n, g.nnz, rpd, cid)
+    assert total == oracle.aes_sum(g.rowptr, g.colidx)
+    assert mean == oracle.aes(g.rowptr, g.colidx)
+    assert want == oracle.should_reorder(g.rowptr, g.colidx)
+
+
 def test_errors_are_reported():
     g = config_graph(1)
     rpd, cid = _dev_csr(g.rowptr, g.colidx)
