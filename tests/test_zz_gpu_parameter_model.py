@@ -1,6 +1,7 @@
 """The parameter model (Sec. 6, re-derived for this GPU) against measurement, the way Sec. 7.5 of the
 paper validates its own: the configuration the model picks must run close to the best of a sweep
-over the neighbor-group size and the dimension workers.  Timing test: the margins are wide."""
+over the neighbor-group size and the dimension workers.  Timing test: the margins are wide, and the
+file name makes it the last one collected, so that a noisy machine cannot hide other tests."""
 import numpy as np
 import pytest
 import torch
@@ -16,17 +17,21 @@ if torch.cuda.is_available():
 MARGIN = 1.25  # model's pick within 25 % of the best point of the sweep
 
 
-def _time_us(fn, reps=5):
+def _time_us(fn, reps=5, rounds=3):
+    """Best of `rounds` means over `reps` calls: a disturbance from outside lengthens a run, never shortens it."""
     for _ in range(2):
         fn()
-    torch.cuda.synchronize()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(reps):
-        fn()
-    b.record()
-    torch.cuda.synchronize()
-    return a.elapsed_time(b) / reps * 1e3
+    best = float("inf")
+    for _ in range(rounds):
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        best = min(best, a.elapsed_time(b) / reps * 1e3)
+    return best
 
 
 def _sweep(g, dim, eps, ew, ngs_list, dw_list):
