@@ -9,7 +9,8 @@ so that the two can be compared bit for bit:
 state    every node belongs to a community, named after one of its nodes (the root); a community
          has a total degree `degw`, a `size`, and an order of its nodes (`pos`, 0-based, root first);
          between communities there are weighted edges (number of original entries, both directions).
-round 1. score of community u towards a neighbouring community v:
+per merge round:
+      1. score of community u towards a neighbouring community v:
             S(u, v) = w(u, v) * M2 - degw(u) * degw(v)      (M2 = entries of the clean graph; this is
          the modularity gain of the merge up to a positive factor).  u proposes to the v with the
          largest S, the smallest id among equals, provided that S > 0.

@@ -14,9 +14,9 @@ def _csr(n, undirected):
 
 
 def test_path_of_three_nodes_worked_by_hand():
-    # 0 - 1 - 2: M2 = 4, degrees 1, 2, 1, every score 1*4 - 1*2 = 2.  Round 1: 0 -> 1, 1 -> 0 (smallest id among
+    # 0 - 1 - 2: M2 = 4, degrees 1, 2, 1, every score 1*4 - 1*2 = 2.  First pass: 0 -> 1, 1 -> 0 (smallest id among
     # equals), 2 -> 1; 0 and 1 propose to each other, 0 stays and 1 joins it; 2 waits because 1 moves.
-    # Round 2: {0,1} (degree 3) and {2}: 1*4 - 3*1 = 1 > 0, they propose to each other, 2 joins.  Order 0, 1, 2.
+    # Second pass: {0,1} (degree 3) and {2}: 1*4 - 3*1 = 1 > 0, they propose to each other, 2 joins.  Order 0, 1, 2.
     rp, ci = _csr(3, [(0, 1), (1, 2)])
     perm, iperm, rounds = oracle.parallel_reorder(rp, ci)
     assert perm.tolist() == [0, 1, 2] and iperm.tolist() == [0, 1, 2] and rounds == 2
@@ -24,7 +24,7 @@ def test_path_of_three_nodes_worked_by_hand():
 
 def test_path_with_the_middle_node_numbered_last_worked_by_hand():
     # 0 - 2 - 1: 0 -> 2, 1 -> 2, 2 -> 0 (smallest id among equals).  0 and 2 propose to each other: 0 stays,
-    # 2 joins 0 and gets position 1; node 1 waits (its target moves).  Round 2: {0,2} and {1}: 4 - 3 > 0, 1 joins
+    # 2 joins 0 and gets position 1; node 1 waits (its target moves).  Second pass: {0,2} and {1}: 4 - 3 > 0, 1 joins
     # at position 2.  New ids: node 0 -> 0, node 2 -> 1, node 1 -> 2.
     rp, ci = _csr(3, [(0, 2), (2, 1)])
     perm, iperm, rounds = oracle.parallel_reorder(rp, ci)
