@@ -27,6 +27,16 @@ def test_library_exports_every_declared_symbol():
     assert gnn.gnn_strerror(0) == "ok" and "CSR" in gnn.gnn_strerror(-2)
 
 
+def test_header_is_plain_c():
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                        os.path.join(ROOT, "include", "gnn.h")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_host_argument_validation():
     lib = gnn.load()
     rp = np.array([0, 1, 2], dtype=np.int32)
