@@ -320,3 +320,38 @@ def test_gcn_layer_in_a_workspace_without_room_for_partial_rows():
     torch.cuda.synchronize()
     gnn.gnn_workspace_status(tight)
     assert_parity(out.cpu().numpy(), ref, ab, "gcn layer 16->22, tight workspace")
+
+
+@pytest.mark.parametrize("kind", ["gcn", "gin"])
+def test_model_forward_captured_in_a_hip_graph_replays_like_the_eager_call(kind):
+    # the device entry points only enqueue kernels (no memset nodes, no synchronisation), so a caller can
+    # capture them; every replay, with eager work and new inputs in between, must equal the eager call
+    g = config_graph(2, shrink=4) if kind == "gcn" else config_graph(3, shrink=8)
+    dims = [24, 16, 5] if kind == "gcn" else [32, 32, 32]
+    ew = oracle.gcn_norm(g.rowptr, g.colidx) if kind == "gcn" else None
+    G = DeviceGraph(g.rowptr, g.colidx, ew)
+    Ws = [dev(glorot(dims[i], dims[i + 1], seed=40 + i)) for i in range(len(dims) - 1)]
+    X = dev(features(g.n, dims[0], seed=50))
+    out = torch.empty(g.n, dims[-1], device="cuda")
+    mws = torch.empty(gnn.gnn_model_workspace_bytes(g.n, g.nnz, dims, 0), dtype=torch.uint8, device="cuda")
+    ngs, _, _ = gnn.gnn_decide(g.n, g.nnz, 0, dims[0])
+    gnn.gnn_partition_build(g.n, g.nnz, G.rowptr, ngs, mws)
+    call = gnn.ModelCall(gnn.GNN_GCN if kind == "gcn" else gnn.GNN_GIN, g.n, g.nnz, G.rowptr, G.colidx, G.ew, 0.1, X, dims,
+                         Ws, None, out, ngs, 0, 0, gnn.GNN_FLAG_REUSE_PARTITION, mws)
+    call()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+        call()
+    for k in range(3):
+        X.copy_(dev(features(g.n, dims[0], seed=60 + k)))  # eager work between the replays
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = out.clone()
+        out.fill_(float("nan"))
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(out, replayed), f"replay {k} differs from the eager call"
+        assert not torch.isnan(replayed).any()
+    gnn.gnn_workspace_status(mws)
