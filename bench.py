@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--train", action="store_true",
                     help="also time a training step (forward + gnn_layer_backward of every layer, no optimizer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured ceilings (device copy, stream read, bare row gathers) reported beside the peak")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, the known-size kernel against which the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled")
@@ -337,6 +339,42 @@ def main():
         train_ms = (time.perf_counter() - tt) * 1e3 / args.steps
         gnn.gnn_workspace_status(bws)
 
+    # ---- what the memory system delivers on this machine, beside the published peak: a plain device copy,
+    # a read-only stream, a bare gather of uniformly random rows of this X and of this graph's own index
+    # stream (the aggregation kernel's loads without tuples, reduction and stores)
+    ceilings = None
+    if not args.no_ceilings:
+        def timed_us(fn, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps * 1e3
+
+        sink = torch.zeros(1, device="cuda")
+        big = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB
+        half = big[: 1 << 26]
+        dst = torch.empty(1 << 26, dtype=torch.float32, device="cuda")
+        t_copy = timed_us(lambda: dst.copy_(half))
+        t_read = timed_us(lambda: gnn.gnn_bench_stream_read(big, sink))
+        ceilings = {"device_copy_256MiB_GBps": 2 * half.numel() * 4 / t_copy / 1e3,
+                    "stream_read_1GiB_GBps": big.numel() * 4 / t_read / 1e3}
+        del big, half, dst
+        if head_dim in (4, 8, 16, 32, 64, 128, 256) and nnz >= 8:
+            rnd = torch.randint(0, n, (nnz,), dtype=torch.int32, device="cuda")
+            t_rnd = timed_us(lambda: gnn.gnn_bench_gather_rows(n, head_dim, Xh, rnd, sink))
+            t_own = timed_us(lambda: gnn.gnn_bench_gather_rows(n, head_dim, Xh, ci, sink))
+            row_bytes = (nnz // 8) * 8 * head_dim * 4
+            ceilings.update({"gather_dim": head_dim,
+                             "gather_uniform_random_rows_GBps": row_bytes / t_rnd / 1e3,
+                             "gather_graph_colidx_GBps": row_bytes / t_own / 1e3,
+                             "gather_graph_colidx_us": t_own})
+            del rnd
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -365,6 +403,14 @@ def main():
              (args.flags & 64 or (nnz / max(n, 1) < 8 and not args.flags & (4 | 8 | 16))))
     if fused:
         kname = "k_gin_layer_fused (aggregation + Update GEMM in one kernel)"
+    traffic = (MEASURED_TRAFFIC_BYTES.get((cfg, ngs, bool(args.renumber)))
+               if args.replicate == 1 and not args.hidden and not args.flags and not fused and
+               args.variant == "default" and not args.renumber_device else None)
+    if ceilings is not None and traffic is not None:
+        # bytes beyond L2 per second against what a bare random gather of rows reaches on this machine
+        ceilings["traffic_GBps"] = traffic / (dom_ms * 1e-3) / 1e9
+        if "gather_uniform_random_rows_GBps" in ceilings:
+            ceilings["traffic_frac_of_random_gather"] = ceilings["traffic_GBps"] / ceilings["gather_uniform_random_rows_GBps"]
     rec = {
         "metric": "aggregation edges*dim/s over one model forward (aggregations + Update GEMMs)",
         "value": value,
@@ -384,10 +430,9 @@ def main():
                    "renumbered": bool(args.renumber), "flags": args.flags, "id_order": args.variant},
         "roofline": {"bound": "hbm", "kernel": f"{kname} ({kind.upper()}, Dim {dom_dim})", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": (MEASURED_TRAFFIC_BYTES.get((cfg, ngs, bool(args.renumber)))
-                                 if args.replicate == 1 and not args.hidden and not args.flags and not fused and
-                                 args.variant == "default" else None),
-                     "algorithmic_bytes_per_launch": dom_bytes, "avg_kernel_ms": dom_ms},
+                     "traffic": traffic,
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_kernel_ms": dom_ms,
+                     "measured_ceilings": ceilings},
         "cpu_baseline": cpu,
         "aggregation_kernel_ms_per_layer": [float(x) for x in agg_ms_layers],
         "aggregation_only_edges_dim_per_s": float(nnz) * dom_dim / (dom_ms * 1e-3),

@@ -306,6 +306,19 @@ int gnn_aes_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t 
  * perm int32[n]. */
 int gnn_permute_rows(int32_t n, int32_t dim, const int32_t *perm, const float *X, float *Y, void *stream);
 
+/* ---- measuring kernels -------------------------------------------------------------- */
+/* What the memory system delivers, for a benchmark to quote beside the published peak (the roofline
+ * of the aggregation, Sec. 7 of the paper reports its bandwidth the same way).  Both only enqueue a
+ * kernel; the caller times it.  sink: DEVICE float[1], never written for finite data.
+ * gnn_bench_stream_read: reads `bytes` (16-byte aligned src) once, sequentially.
+ * gnn_bench_gather_rows: teams of dim/4 lanes read the rows idx[0..nidx) of X[n, dim] with 16-byte
+ * loads, eight rows in flight per team (the aggregation kernel's loads without its tuples, reduction
+ * and stores); dim in {4, 8, ..., 256}; 0 <= idx[k] < n is the caller's duty; nidx is rounded down to
+ * a multiple of 8. */
+int gnn_bench_stream_read(const void *src, size_t bytes, float *sink, void *stream);
+int gnn_bench_gather_rows(int32_t n, int32_t dim, const float *X, const int32_t *idx, int64_t nidx, float *sink,
+                          void *stream);
+
 /* ---- diagnostics ------------------------------------------------------------------ */
 const char *gnn_strerror(int code);
 int gnn_last_hip_error(void);

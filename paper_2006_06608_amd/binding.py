@@ -13,6 +13,7 @@ __all__ = [
     "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_FLAG_NO_FUSION", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
     "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall", "AggregateCall",
     "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
+    "gnn_bench_stream_read", "gnn_bench_gather_rows",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
@@ -42,6 +43,7 @@ _SYMBOLS = [
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
     "gnn_last_hip_error", "gnn_version", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
     "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
+    "gnn_bench_stream_read", "gnn_bench_gather_rows",
 ]
 
 
@@ -469,3 +471,18 @@ def gnn_aes_device(n, nnz, rowptr, colidx, stream=None):
                                ctypes.byref(total), ctypes.byref(mean), ctypes.byref(want), _stream(stream))
     _check(rc, "gnn_aes_device")
     return int(total.value), float(mean.value), bool(want.value)
+
+
+# ------------------------------------------------------------------ measuring kernels
+def gnn_bench_stream_read(src, sink, stream=None):
+    """Enqueues one sequential read of the whole float32 DEVICE tensor src (sink: float32 DEVICE tensor, 1 element)."""
+    rc = load().gnn_bench_stream_read(_dev(src, "float32", "src"), _sz(src.numel() * 4), _dev(sink, "float32", "sink"),
+                                      _stream(stream))
+    _check(rc, "gnn_bench_stream_read")
+
+
+def gnn_bench_gather_rows(n, dim, X, idx, sink, stream=None):
+    """Enqueues a bare gather of the rows idx (int32 DEVICE tensor) of X[n, dim]."""
+    rc = load().gnn_bench_gather_rows(_i32(n), _i32(dim), _dev(X, "float32", "X"), _dev(idx, "int32", "idx"),
+                                      _i64(idx.numel()), _dev(sink, "float32", "sink"), _stream(stream))
+    _check(rc, "gnn_bench_gather_rows")

@@ -328,3 +328,15 @@ def test_random_graphs_and_parameter_combinations(seed):
         assert e.code == -5 or (flags & gnn.GNN_FLAG_DETERMINISTIC), what
         pytest.skip(f"refused with a documented limit ({e.code}): {what}")
     assert_parity(got, ref, ab, what)
+
+
+def test_measuring_kernels_run_and_check_their_arguments():
+    X = torch.ones(1000, 64, device="cuda")
+    idx = torch.randint(0, 1000, (4096,), dtype=torch.int32, device="cuda")
+    sink = torch.zeros(1, device="cuda")
+    gnn.gnn_bench_stream_read(X, sink)
+    gnn.gnn_bench_gather_rows(1000, 64, X, idx, sink)
+    torch.cuda.synchronize()
+    assert sink.item() == 0.0  # never written for finite data
+    with pytest.raises(gnn.GnnError):
+        gnn.gnn_bench_gather_rows(1000, 96, torch.ones(1000, 96, device="cuda"), idx, sink)  # not a power-of-two team
