@@ -618,7 +618,19 @@ int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const floa
     // K slice whose W rows fit the LDS budget, a multiple of the K chunk
     int kmax = kGemmWFloats / LDW / kGemmKC * kGemmKC;
     if (kmax < kGemmKC) kmax = kGemmKC;
-    const int64_t gx = ntiles < 1024 ? ntiles : 1024;
+    // resident blocks per CU: 4, or up to 6 within the 160 KB of LDS when a wave has four column tiles to
+    // multiply, so that more loads are in flight behind the MFMA work (1,048,576 x 64 x 64: 118 us with
+    // 4 per CU, 112 us with 6, 124 us with 8, of which two wait for LDS; 410,236 x 96 x 16 is fastest with 4)
+    const size_t lds_block = ((size_t)(K < kmax ? (K + kGemmKC - 1) / kGemmKC * kGemmKC : kmax) * LDW +
+                              (size_t)kGemmRows * (kGemmKC + 4)) * sizeof(float);
+    int per_cu = (int)((size_t)150 * 1024 / lds_block);
+    const int most = MT == 4 ? 6 : 4;
+    per_cu = per_cu < 2 ? 2 : (per_cu > most ? most : per_cu);
+    int dev = 0, cus = 0;
+    GNN_HIP_TRY(hipGetDevice(&dev));
+    GNN_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    const int64_t cap = (int64_t)per_cu * (cus > 0 ? cus : 256);
+    const int64_t gx = ntiles < cap ? ntiles : cap;
     const dim3 grid((unsigned)gx, (unsigned)((M + MP - 1) / MP));
     for (int k0 = 0; k0 < K; k0 += kmax) {
         GemmParams p;
