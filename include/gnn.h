@@ -16,7 +16,8 @@
  *     every buffer and the library keeps no state between calls.  The compute entry points
  *     allocate nothing; only the diagnostic calls that copy results to the host
  *     (gnn_block_layout_export, gnn_validate_csr_device) and the one-time graph preparation on
- *     the device (gnn_reorder_device, gnn_apply_perm_csr_device, gnn_aes_device) use temporary device buffers.
+ *     the device (gnn_reorder_device, gnn_apply_perm_csr_device, gnn_csr_transpose_device, gnn_aes_device) use
+ *     temporary device buffers.
  *   - Matrices are row-major fp32; CSR indices are int32 (nnz < 2^31); n * dim is
  *     addressed in 64 bits.  In and out buffers must not alias.
  *   - DEVICE entry points only enqueue work on `stream` (a hipStream_t, NULL = the null
@@ -290,6 +291,9 @@ int gnn_layer_backward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr_t
  * gnn_apply_perm_csr_device: gnn_apply_perm_csr on DEVICE arrays, same result byte for byte.
  * Errors: GNN_EINVAL (perm not a bijection), GNN_ECSR, GNN_EHIP.
  *
+ * gnn_csr_transpose_device: gnn_csr_transpose on DEVICE arrays (the graph gnn_layer_backward wants),
+ * same result byte for byte.  Errors: GNN_EINVAL, GNN_ECSR, GNN_EHIP.
+ *
  * gnn_gcn_norm_device: gnn_gcn_norm on DEVICE arrays, same result byte for byte; only enqueues.
  *
  * gnn_aes_device: Eq. 4 and the rule of Sec. 5.1 on a DEVICE CSR (what gnn_aes and the decision inside
@@ -298,6 +302,8 @@ int gnn_reorder_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int3
                        int32_t *iperm, int32_t max_rounds, int32_t *rounds_out, void *stream);
 int gnn_apply_perm_csr_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,
                               const int32_t *perm, int32_t *rowptr2, int32_t *colidx2, float *val2, void *stream);
+int gnn_csr_transpose_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                             int32_t *rowptr_t, int32_t *colidx_t, float *val_t, void *stream);
 int gnn_gcn_norm_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, float *ew, void *stream);
 int gnn_aes_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, int64_t *aes_sum, double *aes,
                    int *should_reorder, void *stream);

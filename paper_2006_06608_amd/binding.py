@@ -13,7 +13,7 @@ __all__ = [
     "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_FLAG_NO_FUSION", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
     "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall", "AggregateCall",
     "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
-    "gnn_bench_stream_read", "gnn_bench_gather_rows",
+    "gnn_bench_stream_read", "gnn_bench_gather_rows", "gnn_csr_transpose_device",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
@@ -43,7 +43,7 @@ _SYMBOLS = [
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
     "gnn_last_hip_error", "gnn_version", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
     "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
-    "gnn_bench_stream_read", "gnn_bench_gather_rows",
+    "gnn_bench_stream_read", "gnn_bench_gather_rows", "gnn_csr_transpose_device",
 ]
 
 
@@ -486,3 +486,17 @@ def gnn_bench_gather_rows(n, dim, X, idx, sink, stream=None):
     rc = load().gnn_bench_gather_rows(_i32(n), _i32(dim), _dev(X, "float32", "X"), _dev(idx, "int32", "idx"),
                                       _i64(idx.numel()), _dev(sink, "float32", "sink"), _stream(stream))
     _check(rc, "gnn_bench_gather_rows")
+
+
+def gnn_csr_transpose_device(n, nnz, rowptr, colidx, val=None, stream=None):
+    """gnn_csr_transpose on DEVICE tensors.  Returns (rowptr_t, colidx_t) or (rowptr_t, colidx_t, val_t)."""
+    import torch
+    rowptr_t = torch.empty(int(n) + 1, dtype=torch.int32, device=rowptr.device)
+    colidx_t = torch.empty(max(int(nnz), 1), dtype=torch.int32, device=rowptr.device)[: int(nnz)]
+    val_t = None if val is None else torch.empty(max(int(nnz), 1), dtype=torch.float32, device=rowptr.device)[: int(nnz)]
+    rc = load().gnn_csr_transpose_device(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"),
+                                         _dev(colidx, "int32", "colidx"), _dev(val, "float32", "val"),
+                                         _dev(rowptr_t, "int32", "rowptr_t"), _dev(colidx_t, "int32", "colidx_t"),
+                                         _dev(val_t, "float32", "val_t"), _stream(stream))
+    _check(rc, "gnn_csr_transpose_device")
+    return (rowptr_t, colidx_t) if val is None else (rowptr_t, colidx_t, val_t)

@@ -278,6 +278,34 @@ __global__ void k_perm_check(int n, const int *__restrict__ perm, int *__restric
     }
 }
 
+// Transpose: entry e = (i, j) gets the sort key (j, i); the sorted order is the transposed CSR.
+__global__ void k_transpose_keys(int n, int64_t nnz, const int *__restrict__ rowptr, const int *__restrict__ colidx,
+                                 uint64_t *__restrict__ key, int *__restrict__ entry, int *__restrict__ len_t,
+                                 int *__restrict__ bad)
+{
+    GRID_STRIDE(e, nnz) {
+        const int i = row_of(rowptr, n, e);
+        int j = colidx[e];
+        if (j < 0 || j >= n) {  // malformed CSR: reported by the caller
+            *bad = 1;
+            j = 0;
+        } else {
+            atomicAdd(&len_t[j], 1);
+        }
+        key[e] = make_key((uint32_t)j, (uint32_t)i);
+        entry[e] = (int)e;
+    }
+}
+
+__global__ void k_transpose_out(int64_t nnz, const uint64_t *__restrict__ key, const int *__restrict__ entry,
+                                const float *__restrict__ val, int *__restrict__ colidx_t, float *__restrict__ val_t)
+{
+    GRID_STRIDE(k, nnz) {
+        colidx_t[k] = (int)(uint32_t)key[k];
+        if (val) val_t[k] = val[entry[k]];
+    }
+}
+
 // Eq. 4: sum over the stored entries of |row - column|, one atomic per wave.
 __global__ void k_aes_sum(int n, int64_t nnz, const int *__restrict__ rowptr, const int *__restrict__ colidx,
                           unsigned long long *__restrict__ total)
@@ -562,6 +590,58 @@ int gnn_apply_perm_csr_device(int32_t n, int64_t nnz, const int32_t *rowptr, con
         b = tmp_bytes;
         GNN_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(tmp, b, keyA, keyB, entA, entB, (int)nnz, 0, key_bits, s));
         hipLaunchKernelGGL(k_relabel_out, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, nnz, keyB, entB, val, colidx2, val2);
+    }
+    GNN_HIP_TRY(hipGetLastError());
+    GNN_HIP_TRY(hipStreamSynchronize(s));
+    return GNN_OK;
+}
+
+int gnn_csr_transpose_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                             int32_t *rowptr_t, int32_t *colidx_t, float *val_t, void *stream)
+{
+    if (n < 0 || nnz < 0 || nnz >= ((int64_t)1 << 31)) return GNN_EINVAL;
+    if (!rowptr || !rowptr_t || (val && !val_t)) return GNN_EINVAL;
+    if (nnz > 0 && (!colidx || !colidx_t)) return GNN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    Arena mem;
+    uint64_t *keyA, *keyB;
+    int *entA, *entB, *len_t, *bad;
+    mem.want(&keyA, (size_t)nnz);
+    mem.want(&keyB, (size_t)nnz);
+    mem.want(&entA, (size_t)nnz);
+    mem.want(&entB, (size_t)nnz);
+    mem.want(&len_t, (size_t)n + 1);
+    mem.want(&bad, 1);
+    const int key_bits = 32 + bit_length((uint32_t)n);
+    size_t tmp_bytes = 0, b = 0;
+    {
+        uint64_t *k0 = nullptr, *k1 = nullptr;
+        int *v0 = nullptr, *v1 = nullptr;
+        GNN_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(nullptr, b, k0, k1, v0, v1, (int)nnz, 0, key_bits, s));
+        tmp_bytes = b;
+        GNN_HIP_TRY(hipcub::DeviceScan::ExclusiveSum(nullptr, b, v0, v1, n + 1, s));
+        tmp_bytes = b > tmp_bytes ? b : tmp_bytes;
+    }
+    char *tmp;
+    mem.want(&tmp, tmp_bytes);
+    GNN_TRY(mem.commit());
+
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(n + 1)), dim3(kThreads), 0, s, len_t, (int64_t)n + 1, 0);
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(kThreads), 0, s, bad, (int64_t)1, 0);
+    if (nnz > 0)
+        hipLaunchKernelGGL(k_transpose_keys, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, n, nnz, rowptr, colidx, keyA, entA,
+                           len_t, bad);
+    int host_bad = 0;
+    GNN_HIP_TRY(hipMemcpyAsync(&host_bad, bad, sizeof(int), hipMemcpyDeviceToHost, s));
+    GNN_HIP_TRY(hipStreamSynchronize(s));
+    if (host_bad != 0) return GNN_ECSR;
+    b = tmp_bytes;
+    GNN_HIP_TRY(hipcub::DeviceScan::ExclusiveSum(tmp, b, len_t, rowptr_t, n + 1, s));
+    if (nnz > 0) {
+        // stable sort by (column, row): the rows of the transpose come out sorted by column
+        b = tmp_bytes;
+        GNN_HIP_TRY(hipcub::DeviceRadixSort::SortPairs(tmp, b, keyA, keyB, entA, entB, (int)nnz, 0, key_bits, s));
+        hipLaunchKernelGGL(k_transpose_out, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, nnz, keyB, entB, val, colidx_t, val_t);
     }
     GNN_HIP_TRY(hipGetLastError());
     GNN_HIP_TRY(hipStreamSynchronize(s));

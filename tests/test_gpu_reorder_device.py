@@ -109,6 +109,27 @@ def test_device_aes_and_rule_equal_the_oracle(name):
     assert want == oracle.should_reorder(g.rowptr, g.colidx)
 
 
+def test_device_transpose_equals_the_oracle_byte_for_byte():
+    # a directed graph (not its own transpose) with values
+    rng = np.random.default_rng(3)
+    n, m = 5000, 60000
+    src, dst = rng.integers(0, n, size=m), rng.integers(0, n, size=m)
+    order = np.lexsort((dst, src))
+    src, dst = src[order], dst[order]
+    rp = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum(np.bincount(src, minlength=n), out=rp[1:])
+    ci = dst.astype(np.int32)
+    val = rng.standard_normal(m).astype(np.float32)
+    rpd, cid = _dev_csr(rp, ci)
+    rpt, cit, vt = gnn.gnn_csr_transpose_device(n, m, rpd, cid, dev(val))
+    orp, oci, ov = oracle.csr_transpose(rp, ci, val)
+    assert rpt.cpu().numpy().tobytes() == orp.astype(np.int32).tobytes()
+    assert cit.cpu().numpy().tobytes() == oci.astype(np.int32).tobytes()
+    assert vt.cpu().numpy().tobytes() == ov.astype(np.float32).tobytes()
+    rpt2, cit2 = gnn.gnn_csr_transpose_device(n, m, rpd, cid)
+    assert torch.equal(rpt2, rpt) and torch.equal(cit2, cit)
+
+
 def test_errors_are_reported():
     g = config_graph(1)
     rpd, cid = _dev_csr(g.rowptr, g.colidx)
