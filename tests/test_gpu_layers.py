@@ -355,3 +355,24 @@ def test_model_forward_captured_in_a_hip_graph_replays_like_the_eager_call(kind)
         assert torch.equal(out, replayed), f"replay {k} differs from the eager call"
         assert not torch.isnan(replayed).any()
     gnn.gnn_workspace_status(mws)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_update_gemm_random_shapes(seed):
+    # the shape decides among four kernels (streaming, resident W, W travelling with A, K split over
+    # the waves) and their 4- / 16-byte load forms: draw shapes across all of them
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.choice([1, 7, 100, 1000, 5000, 20000, 40000, 70000]) * rng.uniform(0.5, 1.0)) + 1
+    K = int(rng.choice([3, 16, 32, 33, 64, 100, 128, 255, 256, 500, 1433]))
+    M = int(rng.choice([1, 3, 7, 16, 22, 32, 47, 64, 65, 100]))
+    if n * K > 40_000_000:
+        n = 40_000_000 // K
+    A = rng.standard_normal((n, K)).astype(np.float32)
+    W = glorot(K, M, seed=seed)
+    b = rng.standard_normal(M).astype(np.float32) if seed % 2 else None
+    relu = seed % 3 == 0
+    ref, ab = oracle.gemm_bias_act(A, W, b, relu, want_abs=True)
+    out = torch.full((n, M), float("nan"), device="cuda")
+    gnn.gnn_update_gemm(n, K, M, dev(A), dev(W), dev(b), relu, out)
+    torch.cuda.synchronize()
+    assert_parity(out.cpu().numpy(), ref, ab, f"gemm {n}x{K}x{M} seed {seed}")
