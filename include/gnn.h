@@ -56,10 +56,12 @@ extern "C" {
                                        call without this flag: the one-time preparation of Sec. 4.1 */
 #define GNN_FLAG_NO_BLOCK_OPT 2u    /* ablation (Sec. 7.4 "block-level optimization"): no scratch-memory
                                        slots, no leaders; every neighbor group adds to global memory */
-#define GNN_FLAG_XCD_RUNS 4u        /* block-to-tile order that keeps runs of 128 consecutive tiles on one
+#define GNN_FLAG_XCD_RUNS 4u        /* block-to-tile order that keeps runs of 32 consecutive tiles on one
                                        XCD (one L2) instead of dealing consecutive tiles round-robin over
-                                       the eight XCDs.  On a renumbered community graph this cut the bytes
-                                       fetched beyond L2 by 38 % but not the run time, so it is opt-in */
+                                       the eight XCDs: fewer bytes fetched beyond L2 on graphs whose ids
+                                       follow communities, 1-3 % less run time.  The library uses this
+                                       order by itself from ngs = 16 on; the flag asks for it with smaller
+                                       groups too (measured slower there) */
 #define GNN_FLAG_NO_PIPELINE 8u     /* always one block per tile (the general kernel) */
 #define GNN_FLAG_PIPELINE 16u       /* persistent, software-pipelined blocks whenever their requirements
                                        hold (a block serves <= 64 groups, a wave <= 512 index entries);
