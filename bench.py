@@ -364,12 +364,14 @@ def main():
         ceilings = {"device_copy_256MiB_GBps": 2 * half.numel() * 4 / t_copy / 1e3,
                     "stream_read_1GiB_GBps": big.numel() * 4 / t_read / 1e3}
         del big, half, dst
-        if head_dim in (4, 8, 16, 32, 64, 128, 256) and nnz >= 8:
+        # at the width of the kernel the roofline object describes (dom_dim)
+        if any(dom_dim == 4 * (1 << t) * c for t in range(7) for c in range(1, 5)) and nnz >= 8:
+            Xg = Xh if dom_dim == head_dim else torch.randn(n, dom_dim, device="cuda")
             rnd = torch.randint(0, n, (nnz,), dtype=torch.int32, device="cuda")
-            t_rnd = timed_us(lambda: gnn.gnn_bench_gather_rows(n, head_dim, Xh, rnd, sink))
-            t_own = timed_us(lambda: gnn.gnn_bench_gather_rows(n, head_dim, Xh, ci, sink))
-            row_bytes = (nnz // 8) * 8 * head_dim * 4
-            ceilings.update({"gather_dim": head_dim,
+            t_rnd = timed_us(lambda: gnn.gnn_bench_gather_rows(n, dom_dim, Xg, rnd, sink))
+            t_own = timed_us(lambda: gnn.gnn_bench_gather_rows(n, dom_dim, Xg, ci, sink))
+            row_bytes = (nnz // 8) * 8 * dom_dim * 4
+            ceilings.update({"gather_dim": dom_dim,
                              "gather_uniform_random_rows_GBps": row_bytes / t_rnd / 1e3,
                              "gather_graph_colidx_GBps": row_bytes / t_own / 1e3,
                              "gather_graph_colidx_us": t_own})
@@ -409,7 +411,9 @@ def main():
     if ceilings is not None and traffic is not None:
         # bytes beyond L2 per second against what a bare random gather of rows reaches on this machine
         ceilings["traffic_GBps"] = traffic / (dom_ms * 1e-3) / 1e9
-        if "gather_uniform_random_rows_GBps" in ceilings:
+        # (comparable only for rows of whole 128-byte lines: the gather figure counts useful bytes, the
+        # counters fetched sectors)
+        if "gather_uniform_random_rows_GBps" in ceilings and dom_dim * 4 % 128 == 0:
             ceilings["traffic_frac_of_random_gather"] = ceilings["traffic_GBps"] / ceilings["gather_uniform_random_rows_GBps"]
     rec = {
         "metric": "aggregation edges*dim/s over one model forward (aggregations + Update GEMMs)",

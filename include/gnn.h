@@ -319,10 +319,10 @@ int gnn_permute_rows(int32_t n, int32_t dim, const int32_t *perm, const float *X
  * of the aggregation, Sec. 7 of the paper reports its bandwidth the same way).  Both only enqueue a
  * kernel; the caller times it.  sink: DEVICE float[1], never written for finite data.
  * gnn_bench_stream_read: reads `bytes` (16-byte aligned src) once, sequentially.
- * gnn_bench_gather_rows: teams of dim/4 lanes read the rows idx[0..nidx) of X[n, dim] with 16-byte
+ * gnn_bench_gather_rows: teams of lanes read the rows idx[0..nidx) of X[n, dim] with 16-byte
  * loads, eight rows in flight per team (the aggregation kernel's loads without its tuples, reduction
- * and stores); dim in {4, 8, ..., 256}; 0 <= idx[k] < n is the caller's duty; nidx is rounded down to
- * a multiple of 8. */
+ * and stores); dim = 4 x (a power of two up to 64) x (1..4), e.g. 16, 64, 96, 256; 0 <= idx[k] < n is the
+ * caller's duty; nidx is rounded down to a multiple of 8. */
 int gnn_bench_stream_read(const void *src, size_t bytes, float *sink, void *stream);
 int gnn_bench_gather_rows(int32_t n, int32_t dim, const float *X, const int32_t *idx, int64_t nidx, float *sink,
                           void *stream);

@@ -27,9 +27,9 @@ __global__ __launch_bounds__(256) void k_bench_stream_read(const float4 *__restr
     if (acc.x + acc.y + acc.z + acc.w == 1.2345678e38f) sink[0] = acc.x;
 }
 
-// A team of 2^team_log2 lanes reads rows idx[k] of dim = 4 * 2^team_log2 floats, eight rows in flight,
-// as the aggregation kernel's teams do.
-__global__ __launch_bounds__(256) void k_bench_gather_rows(const float *__restrict__ X, int dim, int team_log2,
+// A team of 2^team_log2 lanes reads rows idx[k] of dim = 4 * 2^team_log2 * chunks floats, eight rows in
+// flight per chunk, as the aggregation kernel's teams do.
+__global__ __launch_bounds__(256) void k_bench_gather_rows(const float *__restrict__ X, int dim, int team_log2, int chunks,
                                                            const int *__restrict__ idx, int64_t nidx, float *sink)
 {
     const int tlane = threadIdx.x & ((1 << team_log2) - 1);
@@ -40,12 +40,15 @@ __global__ __launch_bounds__(256) void k_bench_gather_rows(const float *__restri
         int c[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) c[u] = idx[base + u];
-        float4 v[8];
+        for (int ch = 0; ch < chunks; ++ch) {
+            const int d = ((ch << team_log2) + tlane) * 4;
+            float4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4 *>(X + (size_t)(unsigned)c[u] * (unsigned)dim + tlane * 4);
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4 *>(X + (size_t)(unsigned)c[u] * (unsigned)dim + d);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w;
+            for (int u = 0; u < 8; ++u) {
+                acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w;
+            }
         }
     }
     if (acc.x + acc.y + acc.z + acc.w == 1.2345678e38f) sink[0] = acc.x;
@@ -68,11 +71,18 @@ int gnn_bench_stream_read(const void *src, size_t bytes, float *sink, void *stre
 int gnn_bench_gather_rows(int32_t n, int32_t dim, const float *X, const int32_t *idx, int64_t nidx, float *sink, void *stream)
 {
     if (n <= 0 || nidx < 0 || !X || !sink || (nidx > 0 && !idx) || ((uintptr_t)X & 15) != 0) return GNN_EINVAL;
-    int team_log2 = -1;
-    for (int t = 0; t <= 6; ++t)
-        if (dim == (4 << t)) team_log2 = t;
-    if (team_log2 < 0) return GNN_EINVAL;  // dim must be 4, 8, ..., 256: a power-of-two team of 16-byte loads
-    hipLaunchKernelGGL(k_bench_gather_rows, dim3(16384), dim3(256), 0, (hipStream_t)stream, X, dim, team_log2, idx, nidx, sink);
+    // dim = 4 floats x team (a power of two up to 64 lanes) x chunks (1..4), the widest team first
+    int team_log2 = -1, chunks = 0;
+    for (int t = 6; t >= 0 && team_log2 < 0; --t)
+        for (int c = 1; c <= 4; ++c)
+            if (dim == 4 * (1 << t) * c) {
+                team_log2 = t;
+                chunks = c;
+                break;
+            }
+    if (team_log2 < 0) return GNN_EINVAL;
+    hipLaunchKernelGGL(k_bench_gather_rows, dim3(16384), dim3(256), 0, (hipStream_t)stream, X, dim, team_log2, chunks, idx, nidx,
+                       sink);
     GNN_HIP_TRY(hipGetLastError());
     return GNN_OK;
 }

@@ -339,4 +339,6 @@ def test_measuring_kernels_run_and_check_their_arguments():
     torch.cuda.synchronize()
     assert sink.item() == 0.0  # never written for finite data
     with pytest.raises(gnn.GnnError):
-        gnn.gnn_bench_gather_rows(1000, 96, torch.ones(1000, 96, device="cuda"), idx, sink)  # not a power-of-two team
+        gnn.gnn_bench_gather_rows(1000, 44, torch.ones(1000, 44, device="cuda"), idx, sink)  # 11 float4: no team shape
+    gnn.gnn_bench_gather_rows(1000, 96, torch.ones(1000, 96, device="cuda"), idx, sink)  # 8 lanes x 3 chunks
+    torch.cuda.synchronize()
