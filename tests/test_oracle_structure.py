@@ -250,3 +250,38 @@ def test_renumbering_leaves_the_aggregation_unchanged(kind):
         rp2, ci2 = oracle.apply_perm_csr(g.rowptr, g.colidx, perm)
         moved = oracle.aggregate_gcn(rp2, ci2, oracle.gcn_norm(rp2, ci2), oracle.permute_rows(Xf, perm))
         np.testing.assert_allclose(oracle.permute_rows(moved, iperm), base, rtol=0, atol=1e-6)
+
+
+@pytest.mark.parametrize("cfg,shrink", [(1, 1), (4, 32), (5, 64)])
+@pytest.mark.parametrize("ngs,T", [(2, 4), (4, 16), (16, 16), (32, 64)])
+def test_global_flushes_per_block_are_bounded(cfg, shrink, ngs, T):
+    # Sec. 5.2: a node whose groups span blocks costs one global flush of Dim values per (node, block),
+    # however many groups (k * ngs neighbours) of it the block holds.  With groups in CSR order only the
+    # node of a block's first group and the node of its last group can continue outside the block, so a
+    # block flushes at most two partial rows -- what the atomic count of the ablation study measures
+    # and what the two scratch rows per block of the ordered flush rely on.
+    g = config_graph(cfg, shrink=shrink)
+    node, start, end = oracle.ng_partition(g.rowptr, ngs)
+    slot, _, leader = oracle.alg1_layout(node, T, 1)
+    groups_of = np.bincount(node, minlength=g.n)
+    first_group = np.concatenate([[0], np.cumsum(groups_of)[:-1]])
+    flushes, pairs = 0, 0
+    for b0 in range(0, node.size, T):
+        blk = node[b0:b0 + T]
+        leaders = np.flatnonzero(leader[b0:b0 + T])
+        assert leaders.size == np.unique(blk).size          # one leader per (block, node) pair
+        pairs += leaders.size
+        partial = []
+        for l in leaders:
+            v = blk[l]
+            inside = first_group[v] >= b0 and first_group[v] + groups_of[v] <= b0 + blk.size
+            if not inside:
+                partial.append(int(l))
+        assert len(partial) <= 2
+        for l in partial:                                   # only the block's first or last node
+            assert blk[l] == blk[0] or blk[l] == blk[-1]
+        flushes += len(partial)
+    blocks = (node.size + T - 1) // T
+    assert flushes <= 2 * blocks
+    # without block-level accumulation every group would flush: the paper's reduction of atomics
+    assert flushes <= node.size and pairs <= node.size
