@@ -154,3 +154,35 @@ def test_layer_order_gcn_update_first_gin_aggregate_first():
     b = rng.standard_normal(3).astype(np.float32)
     ref2 = np.maximum((G @ X.astype(np.float64)) @ W.astype(np.float64) + b, 0)
     np.testing.assert_allclose(oracle.gin_layer(rp2, ci2, 0.0, X, W, b, True), ref2, rtol=1e-5, atol=1e-5)
+
+
+@pytest.mark.parametrize("cfg,shrink,dim", [(2, 1, 16), (4, 32, 24), (5, 64, 7)])
+def test_oracle_against_a_library_sparse_product(cfg, shrink, dim):
+    """The aggregation is a sparse x dense product: scipy's CSR product in fp64 on graphs of a few
+    thousand to tens of thousands of nodes (brute force covers only tiny ones), GCN weights, GIN self
+    term, and the max / min / mean reductions through scipy's own row operations."""
+    import scipy.sparse as sp
+    from gnn_synth import config_graph, features
+    g = config_graph(cfg, shrink=shrink)
+    n = g.n
+    X = features(n, dim, seed=cfg * 10 + dim)
+    ew = oracle.gcn_norm(g.rowptr, g.colidx)
+    A = sp.csr_matrix((ew.astype(np.float64), g.colidx, g.rowptr), shape=(n, n))
+    ref = (A @ X.astype(np.float64)).astype(np.float32)
+    got = oracle.aggregate_gcn(g.rowptr, g.colidx, ew, X)
+    assert np.abs(got - ref).max() <= 2e-7 * max(1.0, np.abs(ref).max())
+    ones = sp.csr_matrix((np.ones(g.nnz), g.colidx, g.rowptr), shape=(n, n))
+    eps = 0.25
+    ref = ((1.0 + eps) * X.astype(np.float64) + ones @ X.astype(np.float64)).astype(np.float32)
+    got = oracle.aggregate_gin(g.rowptr, g.colidx, eps, X)
+    assert np.abs(got - ref).max() <= 2e-7 * max(1.0, np.abs(ref).max())
+    deg = np.diff(g.rowptr).astype(np.float64)
+    mean = np.divide((ones @ X.astype(np.float64)), deg[:, None], out=np.zeros((n, dim)), where=deg[:, None] > 0)
+    got = oracle.aggregate_reduce(g.rowptr, g.colidx, X, oracle.REDUCE_MEAN)
+    assert np.abs(got - mean.astype(np.float32)).max() <= 2e-7 * max(1.0, np.abs(mean).max())
+    # max over the stored entries of a row: numpy's reduceat over the gathered rows (rows without entries give 0)
+    nonempty = np.flatnonzero(deg > 0)
+    gathered = X[g.colidx]
+    mx = np.zeros((n, dim), dtype=np.float32)
+    mx[nonempty] = np.maximum.reduceat(gathered, g.rowptr[:-1][nonempty].astype(np.int64), axis=0)
+    assert np.array_equal(oracle.aggregate_reduce(g.rowptr, g.colidx, X, oracle.REDUCE_MAX), mx)
