@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
-from .parallel_reorder import parallel_reorder  # noqa: F401  (round-based renumbering, numpy)
+from .parallel_reorder import parallel_reorder, parallel_reorder_numpy  # noqa: F401  (round-based renumbering)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gnn_oracle.c")
@@ -216,29 +216,44 @@ def permute_rows(X, perm) -> np.ndarray:
 # Order inside a layer follows Sec. 3.1: GCN reduces the dimension first (Update, then
 # Aggregation); GIN aggregates at full dimension, then updates.  Values between operations
 # are stored as float.
-def gcn_layer(rowptr, colidx, ew, X, W, b=None, relu: bool = False, want_abs: bool = False):
-    """act(A_hat (X W) + b).  want_abs adds the layer's error scale |A_hat| (|X| |W|) + |b|: the sum of
-    absolute values of all terms of both operations, against which a floating-point evaluation in
-    any order is judged."""
+def _aggregate_f64(rowptr, colidx, w64, X64):
+    """sum_e w[e] * X[col_e,:] in double, nothing rounded to float (error scales only)."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    X64 = np.ascontiguousarray(X64, dtype=np.float64)
+    w64 = None if w64 is None else np.ascontiguousarray(w64, dtype=np.float64)
+    n, dim = rowptr.size - 1, X64.shape[1]
+    out = np.empty((n, dim), dtype=np.float64)
+    _L().orc_aggregate_f64(ctypes.c_int32(n), _p(rowptr), _p(colidx), _p(w64), _p(X64), ctypes.c_int32(dim), _p(out))
+    return out
+
+
+def gcn_layer(rowptr, colidx, ew, X, W, b=None, relu: bool = False, want_abs=False):
+    """act(A_hat (X W) + b).  want_abs=True adds the layer's error scale |A_hat| (|X| |W|) + |b|: the sum
+    of absolute values of all terms of both operations, in double throughout, against which a
+    floating-point evaluation in any order is judged.  want_abs="both" adds, third, the stricter scale
+    of the last operation alone, |A_hat| |fl(X W)| + |b| (fl = the product as stored in float)."""
     if not want_abs:
         H = gemm_bias_act(X, W, None, False)
         return bias_act(aggregate_gcn(rowptr, colidx, ew, H), b, relu)
     H, Habs = gemm_bias_act(X, W, None, False, want_abs=True)
-    Z = aggregate_gcn(rowptr, colidx, ew, H)
-    scale = aggregate_gcn(rowptr, colidx, None if ew is None else np.abs(_f32(ew)), Habs.astype(np.float32)).astype(np.float64)
-    if b is not None:
-        scale = scale + np.abs(_f32(b)).astype(np.float64)
-    return bias_act(Z, b, relu), scale
+    Z, Zabs = aggregate_gcn(rowptr, colidx, ew, H, want_abs=True)
+    babs = 0.0 if b is None else np.abs(_f32(b)).astype(np.float64)
+    scale = _aggregate_f64(rowptr, colidx, None if ew is None else np.abs(_f32(ew)).astype(np.float64), Habs) + babs
+    out = bias_act(Z, b, relu)
+    return (out, scale, Zabs + babs) if want_abs == "both" else (out, scale)
 
 
-def gin_layer(rowptr, colidx, eps, X, W, b=None, relu: bool = False, want_abs: bool = False):
-    """act(((1+eps) X + sum_N X) W + b).  want_abs adds the layer's error scale (|1+eps| |X| + sum_N |X|) |W| + |b|."""
+def gin_layer(rowptr, colidx, eps, X, W, b=None, relu: bool = False, want_abs=False):
+    """act(((1+eps) X + sum_N X) W + b).  want_abs=True adds the layer's error scale
+    (|1+eps| |X| + sum_N |X|) |W| + |b|, in double throughout; want_abs="both" adds, third, the stricter
+    scale of the last operation alone, |fl(aggregate)| |W| + |b|."""
     if not want_abs:
         return gemm_bias_act(aggregate_gin(rowptr, colidx, eps, X), W, b, relu)
     A, Aabs = aggregate_gin(rowptr, colidx, eps, X, want_abs=True)
-    out = gemm_bias_act(A, W, b, relu)
-    scale = gemm_bias_act(Aabs.astype(np.float32), np.abs(_f32(W)), None if b is None else np.abs(_f32(b)), False)
-    return out, scale.astype(np.float64)
+    out, last = gemm_bias_act(A, W, b, relu, want_abs=True)
+    babs = 0.0 if b is None else np.abs(_f32(b)).astype(np.float64)
+    scale = Aabs @ np.abs(_f32(W)).astype(np.float64) + babs
+    return (out, scale, last) if want_abs == "both" else (out, scale)
 
 
 def gcn_model(rowptr, colidx, ew, X, Ws: Sequence[np.ndarray], bs: Optional[Sequence] = None,

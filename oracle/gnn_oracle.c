@@ -10,15 +10,40 @@
  * when the result of an operation (aggregation, dense layer) is stored.  Values
  * between operations are float, as they are on the GPU.
  *
- * Pins (see tests/test_oracle_*.py): dense A.X by brute force on tiny graphs,
- * all-ones closed forms (regular graph -> 1, star graph), linearity, the
- * (1+eps) self term, numpy matmul for the dense layer, the worked
- * neighbor-group example of Sec. 4.1, the invariants of Algorithm 1, the
- * literal values of Eq. 5 / Eq. 6, hand-computed AES values and thresholds,
- * and structural properties of the renumbering (bijection, cliques become
- * contiguous, AES falls on shuffled block-diagonal graphs, one hand trace);
- * max / min / mean: numpy reductions over dense neighbour lists on tiny graphs,
- * closed forms on paths and stars, min <= mean <= max, mean = sum / degree.
+ * Pins (tests/test_oracle_*.py, all run without a GPU), function by function:
+ *   orc_aggregate_gcn     aggregate.py: gcn_matches_dense_product, gcn_is_not_symmetric_in_its_operands,
+ *                         all_ones_features_give_normalised_degree_sums, regular_graph_..._to_one,
+ *                         star_graph_closed_form, linearity_and_eps_term, empty_graph_and_isolated_nodes,
+ *                         oracle_against_a_library_sparse_product; abs_out: layers.py:
+ *                         aggregation_error_scales_are_the_sums_of_absolute_terms
+ *   orc_aggregate_f64     layers.py: gcn_layer_error_scale_equals_the_dense_expression
+ *   orc_aggregate_gin     aggregate.py: gin_matches_dense_product, all_ones..., linearity_and_eps_term,
+ *                         empty_graph_and_isolated_nodes; abs_out as above
+ *   orc_aggregate_reduce  reduce.py: reductions_match_numpy_over_explicit_neighbour_lists,
+ *                         closed_forms_on_a_path_and_a_star, order_relations_and_link_to_the_sum_aggregation
+ *   orc_gemm_bias_act     aggregate.py: gemm_matches_numpy, gemm_identity_and_non_square_orientation;
+ *                         abs_out: layers.py as above
+ *   orc_bias_act          layers.py: bias_act_values_worked_by_hand, bias_is_broadcast_over_rows_not_columns,
+ *                         gcn_layer_with_bias_equals_the_dense_expression
+ *   orc_gcn_norm          aggregate.py: gcn_norm_is_symmetric_bitwise, regular graph -> 1/(k+1), star
+ *   orc_aes_sum, orc_aes_threshold, orc_should_reorder
+ *                         structure.py: aes_hand_computed, aes_thresholds_from_the_rule
+ *   orc_ng_partition      structure.py: paper_worked_example_of_neighbor_groups (tests/golden/
+ *                         ng_partition_example.txt), neighbor_groups_tile_the_csr
+ *   orc_alg1_layout       structure.py: alg1_hand_trace (tests/golden/alg1_trace.txt), alg1_invariants,
+ *                         global_flushes_per_block_are_bounded
+ *   orc_eq5_*, orc_eq6_dw structure.py: eq5_eq6_literal_values
+ *   orc_reorder           structure.py: reorder_hand_trace (tests/golden/reorder_trace.txt),
+ *                         reorder_is_a_bijection_and_deterministic, ..._interleaved_cliques_contiguous,
+ *                         ..._lowers_aes_of_shuffled_block_diagonal_batch, ..._finds_planted_communities,
+ *                         ..._path_graph_keeps_small_span
+ *   orc_apply_perm_csr, orc_permute_rows
+ *                         structure.py: apply_perm_csr_and_permute_rows,
+ *                         renumbering_leaves_the_aggregation_unchanged
+ * The compositions in __init__.py (gcn_layer, gin_layer, gcn_model, gin_model, their error scales,
+ * the backward pass) are pinned by tests/test_oracle_layers.py (dense double-precision expressions,
+ * bias after the aggregation, ReLU after every layer but the last) and tests/test_oracle_backward.py
+ * (finite differences); parallel_reorder.py by tests/test_oracle_parallel_reorder.py.
  * Parity unpinned: none of the functions below.
  */
 #include <math.h>
@@ -45,6 +70,22 @@ void orc_aggregate_gcn(int32_t n, const int32_t *rowptr, const int32_t *colidx, 
             }
             out[(size_t)i * dim + k] = (float)acc;
             if (abs_out) abs_out[(size_t)i * dim + k] = aacc;
+        }
+    }
+}
+
+/* The same sum over doubles: out[i,:] = sum over stored entries e of row i of w[e] * X[colidx[e],:]
+ * (w NULL = unit weights), nothing rounded to float.  Used for the error scale of a GCN layer,
+ * |A_hat| (|X| |W|), whose inner factor is already a double. */
+void orc_aggregate_f64(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w,
+                       const double *X, int32_t dim, double *out)
+{
+    for (int32_t i = 0; i < n; ++i) {
+        for (int32_t k = 0; k < dim; ++k) {
+            double acc = 0.0;
+            for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e)
+                acc += (w ? w[e] : 1.0) * X[(size_t)colidx[e] * dim + k];
+            out[(size_t)i * dim + k] = acc;
         }
     }
 }
@@ -200,33 +241,28 @@ int64_t orc_ng_partition(int32_t n, const int32_t *rowptr, int32_t ngs,
 }
 
 /* ------------------------------------------------------------------ Algorithm 1
- * One worker ("warp" in the paper) per neighbor group, warpPerBlock workers per block.
- * For worker cnt: slot[cnt] = index of its target node's slot among the block's distinct target
- * nodes, sharedAddr[cnt] = slot * Dim (float offset of the slot in the block's scratch memory;
- * the printed algorithm mixes the two, the offset reading is used throughout), leader[cnt] = 1
- * for the first worker of each (block, node) pair. */
+ * What the algorithm assigns, stated as a definition.  Workers (one per neighbor group; the paper's
+ * "warps") are cut into blocks of warpPerBlock consecutive workers.  Inside a block the workers of
+ * one target node are consecutive (groups are stored node by node), so the block's distinct target
+ * nodes can be numbered 0, 1, 2, ... in the order in which they first appear:
+ *   slot[g]   = that number for the target node of worker g: the node's slot in the block's scratch
+ *               memory; its float offset is sharedAddr[g] = slot[g] * Dim (the printed algorithm
+ *               mixes index and offset; the offset reading is used throughout);
+ *   leader[g] = 1 for the first worker of each (block, node) pair, else 0: the one worker that
+ *               moves the slot to global memory. */
 void orc_alg1_layout(int64_t warpNum, const int32_t *nodeID, int32_t warpPerBlock, int32_t Dim,
                      int32_t *slot, int64_t *sharedAddr, uint8_t *leader)
 {
-    int64_t cnt = 0;
-    int32_t local_cnt = 0;
-    int32_t last = 0;
-    while (cnt < warpNum) {
-        leader[cnt] = 0;
-        if (cnt % warpPerBlock == 0) { /* worker at the front of a block */
-            slot[cnt] = local_cnt;
-            last = nodeID[cnt];
-            leader[cnt] = 1;
-        } else if (nodeID[cnt] == last) { /* same target node as its predecessor */
-            slot[cnt] = local_cnt;
-        } else { /* a new target node inside the block */
-            local_cnt++;
-            slot[cnt] = local_cnt;
-            last = nodeID[cnt];
-            leader[cnt] = 1;
+    for (int64_t block_first = 0; block_first < warpNum; block_first += warpPerBlock) {
+        int64_t block_end = block_first + warpPerBlock < warpNum ? block_first + warpPerBlock : warpNum;
+        int32_t distinct = 0; /* target nodes seen so far in this block */
+        for (int64_t g = block_first; g < block_end; ++g) {
+            int opens_node = (g == block_first) || (nodeID[g] != nodeID[g - 1]);
+            if (opens_node) ++distinct;
+            slot[g] = distinct - 1;
+            sharedAddr[g] = (int64_t)slot[g] * Dim;
+            leader[g] = opens_node ? 1 : 0;
         }
-        sharedAddr[cnt] = (int64_t)slot[cnt] * Dim;
-        if ((++cnt) % warpPerBlock == 0) local_cnt = 0; /* next worker opens a new block */
     }
 }
 

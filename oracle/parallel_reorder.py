@@ -3,8 +3,15 @@ INFRASTRUCTURE ONLY.
 
 Sec. 5.1 of the paper asks for node ids that follow communities found by merging for modularity; it
 does not fix the merge schedule.  The GPU library also offers a schedule made of synchronous rounds
-(every community looks at the same state), which this file restates in plain numpy, integers only,
-so that the two can be compared bit for bit:
+(every community looks at the same state), which this file restates in plain Python, integers only,
+so that the two can be compared bit for bit.
+
+Two forms of the same schedule live here.  `parallel_reorder` is THE oracle: dictionaries and loops,
+one community at a time, each step of the list below written out so that it can be checked by eye;
+it serves graphs of up to some ten thousand nodes.  `parallel_reorder_numpy` takes the same steps
+with sorts and segmented sums; it is pinned to the loop form (equal permutations on random graphs of
+up to a few thousand nodes, tests/test_oracle_parallel_reorder.py) and only stands in for it where
+the loop form would take minutes (the full-size community graph).
 
 state    every node belongs to a community, named after one of its nodes (the root); a community
          has a total degree `degw`, a `size`, and an order of its nodes (`pos`, 0-based, root first);
@@ -30,9 +37,69 @@ from typing import Tuple
 
 import numpy as np
 
-
 def parallel_reorder(rowptr, colidx, max_rounds: int = 64) -> Tuple[np.ndarray, np.ndarray, int]:
     """Returns perm (old -> new), iperm (new -> old), both int32[n], and the number of rounds that merged."""
+    rowptr = np.asarray(rowptr, dtype=np.int64)
+    colidx = np.asarray(colidx, dtype=np.int64)
+    n = rowptr.size - 1
+    # the clean graph: distinct neighbours other than the node itself, unit weights
+    adj = [dict() for _ in range(n)]
+    for i in range(n):
+        for j in colidx[rowptr[i]:rowptr[i + 1]]:
+            if int(j) != i:
+                adj[i][int(j)] = 1
+    M2 = sum(len(a) for a in adj)
+    degw = [len(a) for a in adj]
+    members = [[i] for i in range(n)]      # node order of every community, root first
+    alive = [True] * n                     # still the root of a community
+    rounds = 0
+    for _ in range(max_rounds):
+        # 1. every community proposes to the neighbour of largest score, the smallest id among equals
+        best = list(range(n))
+        for u in range(n):
+            if not alive[u]:
+                continue
+            top = None
+            for v in sorted(adj[u]):
+                s = adj[u][v] * M2 - degw[u] * degw[v]
+                if top is None or s > top[0]:
+                    top = (s, v)
+            if top is not None and top[0] > 0:
+                best[u] = top[1]
+        # 2. of two communities that propose to each other the smaller id stays
+        prop = list(best)
+        for u in range(n):
+            if best[u] != u and best[best[u]] == u and u < best[u]:
+                prop[u] = u
+        # 3. only proposals to a community that does not move itself are carried out
+        joins = [u for u in range(n) if prop[u] != u and prop[prop[u]] == prop[u]]
+        if not joins:
+            break
+        rounds += 1
+        # 4. joiners are appended to their target by ascending id; degrees add up; edges are renamed
+        target = {u: prop[u] for u in joins}
+        for u in sorted(joins):
+            t = target[u]
+            members[t] += members[u]
+            degw[t] += degw[u]
+            alive[u] = False
+        new_adj = [dict() for _ in range(n)]
+        for u in range(n):
+            for v, wt in adj[u].items():
+                a, b = target.get(u, u), target.get(v, v)
+                if a != b:
+                    new_adj[a][b] = new_adj[a].get(b, 0) + wt
+        adj = new_adj
+    # new ids: communities by ascending root id, inside a community by position
+    order = [v for r in range(n) if alive[r] for v in members[r]]
+    iperm = np.array(order, dtype=np.int32).reshape(n)
+    perm = np.empty(n, dtype=np.int32)
+    perm[iperm] = np.arange(n, dtype=np.int32)
+    return perm, iperm, rounds
+
+
+def parallel_reorder_numpy(rowptr, colidx, max_rounds: int = 64) -> Tuple[np.ndarray, np.ndarray, int]:
+    """The vectorised cross-check of parallel_reorder (same steps, same result); for large graphs."""
     rowptr = np.asarray(rowptr, dtype=np.int64)
     colidx = np.asarray(colidx, dtype=np.int64)
     n = rowptr.size - 1

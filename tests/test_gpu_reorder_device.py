@@ -1,4 +1,4 @@
-"""Graph preparation on the device: the round-based renumbering against its numpy oracle (bit-exact),
+"""Graph preparation on the device: the round-based renumbering against its oracle, the loop form of oracle/parallel_reorder.py (bit-exact, up to the full-size community graph),
 the device CSR relabelling and GCN weights against the oracle (byte-equal), and the whole on-device
 pipeline feeding an aggregation."""
 import numpy as np

@@ -1,4 +1,5 @@
-"""Pins for the oracle of the round-based renumbering (oracle/parallel_reorder.py): hand-worked
+"""Pins for the oracle of the round-based renumbering (oracle/parallel_reorder.py; the loop form is the
+oracle, the numpy form its cross-check for large graphs): hand-worked
 examples, properties every renumbering must have, recovery of planted communities, and the
 locality it buys compared with the sequential merge order."""
 import numpy as np
@@ -52,53 +53,14 @@ def test_no_edges_no_change_and_self_loops_and_duplicates_are_ignored():
     assert oracle.parallel_reorder(rp, ci)[0].tolist() == [0, 2, 1]
 
 
-def _reference_rounds(n, rowptr, colidx, max_rounds=64):
-    """The same schedule with dictionaries and loops, one community at a time (tiny graphs only)."""
-    adj = [dict() for _ in range(n)]
-    for i in range(n):
-        for j in colidx[rowptr[i]:rowptr[i + 1]]:
-            if int(j) != i:
-                adj[i][int(j)] = 1
-    M2 = sum(len(a) for a in adj)
-    degw = [len(a) for a in adj]
-    members = [[i] for i in range(n)]
-    alive = [True] * n
-    for _ in range(max_rounds):
-        best = list(range(n))
-        for u in range(n):
-            if not alive[u]:
-                continue
-            top = None
-            for v in sorted(adj[u]):
-                s = adj[u][v] * M2 - degw[u] * degw[v]
-                if top is None or s > top[0]:
-                    top = (s, v)
-            if top is not None and top[0] > 0:
-                best[u] = top[1]
-        prop = list(best)
-        for u in range(n):
-            if best[u] != u and best[best[u]] == u and u < best[u]:
-                prop[u] = u
-        joins = [u for u in range(n) if prop[u] != u and prop[prop[u]] == prop[u]]
-        if not joins:
-            break
-        target = {u: prop[u] for u in joins}
-        for u in sorted(joins):
-            t = target[u]
-            members[t] += members[u]
-            degw[t] += degw[u]
-            alive[u] = False
-        new_adj = [dict() for _ in range(n)]
-        for u in range(n):
-            for v, wt in adj[u].items():
-                a, b = target.get(u, u), target.get(v, v)
-                if a != b:
-                    new_adj[a][b] = new_adj[a].get(b, 0) + wt
-        adj = new_adj
-    order = [v for r in range(n) if alive[r] for v in members[r]]
-    perm = np.empty(n, dtype=np.int32)
-    perm[np.array(order, dtype=np.int64)] = np.arange(n, dtype=np.int32)
-    return perm
+@pytest.mark.parametrize("form", ["loop", "numpy"])
+def test_hand_worked_examples_hold_for_both_forms(form):
+    f = oracle.parallel_reorder if form == "loop" else oracle.parallel_reorder_numpy
+    assert f(*_csr(3, [(0, 1), (1, 2)]))[0].tolist() == [0, 1, 2]
+    perm, iperm, rounds = f(*_csr(3, [(0, 2), (2, 1)]))
+    assert perm.tolist() == [0, 2, 1] and iperm.tolist() == [0, 2, 1] and rounds == 2
+    perm, _, _ = f(*_csr(6, [(0, 2), (2, 4), (0, 4), (1, 3), (3, 5), (1, 5), (4, 1)]))
+    assert sorted(perm[[0, 2, 4]].tolist()) == [0, 1, 2] and sorted(perm[[1, 3, 5]].tolist()) == [3, 4, 5]
 
 
 @pytest.mark.parametrize("seed", range(12))
@@ -108,10 +70,29 @@ def test_numpy_form_equals_the_loop_form_on_small_random_graphs(seed):
     m = int(rng.integers(1, 4 * n))
     a, b = rng.integers(0, n, size=m), rng.integers(0, n, size=m)
     rp, ci = _csr(n, zip(a, b))
-    perm, iperm, _ = oracle.parallel_reorder(rp, ci)
+    perm, iperm, rounds = oracle.parallel_reorder(rp, ci)
     assert np.array_equal(np.sort(perm), np.arange(n)) and np.array_equal(iperm[perm], np.arange(n))
-    assert np.array_equal(perm, _reference_rounds(n, rp, ci))
+    fast = oracle.parallel_reorder_numpy(rp, ci)
+    assert np.array_equal(perm, fast[0]) and np.array_equal(iperm, fast[1]) and rounds == fast[2]
     assert np.array_equal(perm, oracle.parallel_reorder(rp, ci)[0])  # deterministic
+
+
+@pytest.mark.parametrize("name,cfg,shrink", [("citation", 1, 1), ("batch", 3, 8), ("community", 4, 64), ("rmat", 5, 128)])
+def test_numpy_form_equals_the_loop_form_on_graphs_of_thousands_of_nodes(name, cfg, shrink):
+    g = config_graph(cfg, shrink=shrink)
+    assert g.n >= 2000
+    perm, iperm, rounds = oracle.parallel_reorder(g.rowptr, g.colidx)
+    fast = oracle.parallel_reorder_numpy(g.rowptr, g.colidx)
+    assert np.array_equal(perm, fast[0]) and np.array_equal(iperm, fast[1]) and rounds == fast[2]
+    assert rounds >= 3
+
+
+def test_max_rounds_cuts_both_forms_at_the_same_state():
+    g = config_graph(1)
+    for r in (1, 2, 5):
+        a = oracle.parallel_reorder(g.rowptr, g.colidx, max_rounds=r)
+        b = oracle.parallel_reorder_numpy(g.rowptr, g.colidx, max_rounds=r)
+        assert a[2] == r and np.array_equal(a[0], b[0]) and b[2] == r
 
 
 def test_planted_cliques_come_out_contiguous():
