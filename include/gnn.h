@@ -44,7 +44,7 @@ extern "C" {
 #define GNN_EWORKSPACE (-3) /* workspace missing, misaligned (256 B) or too small         */
 #define GNN_EHIP (-4)       /* a HIP runtime call failed                                  */
 #define GNN_ELIMIT (-5)     /* parameters exceed a documented limit (LDS budget, sizes)   */
-#define GNN_ESTALE (-6)     /* GNN_FLAG_REUSE_PARTITION but the workspace holds no partition for (n, nnz, ngs) */
+#define GNN_ESTALE (-6)     /* GNN_FLAG_REUSE_PARTITION but the workspace holds no partition for (rowptr, n, nnz, ngs) */
 
 /* ---- layer kinds (Sec. 3.1) ------------------------------------------------------ */
 #define GNN_GCN 0 /* Update (GEMM), then Aggregation (Eq. 2), then bias/activation */
@@ -53,7 +53,12 @@ extern "C" {
 /* ---- flags of the DEVICE entry points -------------------------------------------- */
 #define GNN_FLAG_REUSE_PARTITION 1u /* workspace already holds the neighbor partition for this
                                        (rowptr, ngs), built by gnn_partition_build or by an earlier
-                                       call without this flag: the one-time preparation of Sec. 4.1 */
+                                       call without this flag: the one-time preparation of Sec. 4.1.
+                                       The partition is tied to the ADDRESS of the rowptr array it was
+                                       built from (and to n, nnz, ngs): a call with another rowptr array
+                                       computes nothing and gnn_workspace_status reports GNN_ESTALE.
+                                       Changing the contents of that array in place is the caller's
+                                       responsibility (build the partition again) */
 #define GNN_FLAG_NO_BLOCK_OPT 2u    /* ablation (Sec. 7.4 "block-level optimization"): no scratch-memory
                                        slots, no leaders; every neighbor group adds to global memory */
 #define GNN_FLAG_XCD_RUNS 4u        /* block-to-tile order that keeps runs of 32 consecutive tiles on one
@@ -130,8 +135,13 @@ int gnn_csr_transpose(int32_t n, const int32_t *rowptr, const int32_t *colidx, c
                       int32_t *rowptr_t, int32_t *colidx_t, float *val_t);
 
 /* The parameter model re-derived for 256 CUs / 64-lane wavefronts / 160 KB LDS (Sec. 6).
- * Pure host function.  max_degree may be 0 (unknown).  Outputs: ngs (neighbor-group size),
- * dw (lanes that share one neighbor row), waves_per_block. */
+ * Pure host function.  max_degree may be 0 (unknown).  ngs (neighbor-group size), dw (lanes that
+ * share one neighbor row) and waves_per_block are IN/OUT: a positive value on entry is the caller's
+ * choice and is kept, 0 asks for the model's choice given the others -- with max_degree = 0 exactly
+ * what the DEVICE entry points do with their own ngs / dw / waves_per_block arguments (they cannot
+ * read the longest row of a device CSR without synchronising).  The model's choices always fit the
+ * scratch-memory limit of a block (see gnn_aggregate_gcn) for Dim up to 15,000.
+ * Errors: GNN_EINVAL (NULL, negative, dw not a power of two <= 64, waves_per_block > 16). */
 int gnn_decide(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, int32_t *ngs, int32_t *dw,
                int32_t *waves_per_block);
 
@@ -186,7 +196,10 @@ int gnn_validate_csr_device(int32_t n, int64_t nnz, const int32_t *rowptr, const
  *   dw   dimension workers: lanes sharing one neighbor row, a power of two <= 64, 0 = model's
  *        choice (Sec. 4.2); a wavefront serves 64/dw neighbor groups side by side
  *   waves_per_block  1..16, 0 = model's choice (the paper's user-chosen threads-per-block / 64)
- * Errors: GNN_EINVAL, GNN_EWORKSPACE, GNN_ELIMIT (LDS need above 64 KB), GNN_EHIP. */
+ * Errors: GNN_EINVAL, GNN_EWORKSPACE, GNN_EHIP, and GNN_ELIMIT when a block's scratch memory would
+ * exceed 64 KB: with T = waves_per_block * 64 / dw groups per block the need is
+ *   round_up_16(4 * (16 + T + T * ngs * (ew ? 2 : 1))) + 4 * T * dim + 256 * waves_per_block  bytes
+ * (the model's own choices never exceed it; caller-chosen ngs / dw / waves_per_block can). */
 int gnn_aggregate_gcn(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
                       const float *ew, const float *X, float *out, int32_t dim, int32_t ngs,
                       int32_t dw, int32_t waves_per_block, uint32_t flags, void *workspace,

@@ -186,8 +186,9 @@ def gnn_csr_transpose(rowptr: np.ndarray, colidx: np.ndarray, val: Optional[np.n
     return (rp2, ci2) if val is None else (rp2, ci2, v2)
 
 
-def gnn_decide(n: int, nnz: int, max_degree: int, dim: int) -> Tuple[int, int, int]:
-    a, b, c = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+def gnn_decide(n: int, nnz: int, max_degree: int, dim: int, ngs: int = 0, dw: int = 0,
+               waves_per_block: int = 0) -> Tuple[int, int, int]:
+    a, b, c = ctypes.c_int32(ngs), ctypes.c_int32(dw), ctypes.c_int32(waves_per_block)
     rc = load().gnn_decide(_i32(n), _i64(nnz), _i32(max_degree), _i32(dim), ctypes.byref(a), ctypes.byref(b),
                            ctypes.byref(c))
     _check(rc, "gnn_decide")

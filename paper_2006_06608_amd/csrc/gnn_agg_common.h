@@ -35,6 +35,7 @@ struct AggParams {
     int extra_blocks;  // one-block-per-tile kernel: blocks appended to the grid for the rows without entries
     int64_t tile_blocks;  // one-block-per-tile kernel: blocks that serve tiles
     int64_t nnz;
+    uint64_t rowptr_key;  // address of the caller's rowptr: the graph the stored partition must belong to
 };
 
 // Reduction over the neighbour rows (Sec. 3.1): sum (GCN, GIN; mean is a sum scaled when the row is
@@ -146,6 +147,7 @@ struct HeaderVals {
     uint32_t magic;
     int32_t n, ngs, status;
     int64_t nnz, num_ng;
+    uint64_t rowptr_addr;
 };
 
 __device__ __forceinline__ HeaderVals load_header(const WsHeader *hdr)
@@ -157,12 +159,16 @@ __device__ __forceinline__ HeaderVals load_header(const WsHeader *hdr)
     h.status = hdr->status;
     h.nnz = hdr->nnz;
     h.num_ng = hdr->num_ng;
+    h.rowptr_addr = hdr->rowptr_addr;
     return h;
 }
 
 __device__ __forceinline__ bool header_vals_ok(const HeaderVals &h, const AggParams &p)
 {
-    return (h.magic == kMagic) & (h.status == GNN_OK) & (h.ngs == p.ngs) & (h.n == p.n) & (h.nnz == p.nnz);
+    // (n, nnz, ngs) alone would accept the partition of another graph of the same size -- a renumbered
+    // graph keeps both -- so the partition is also tied to the rowptr array it was built from
+    return (h.magic == kMagic) & (h.status == GNN_OK) & (h.ngs == p.ngs) & (h.n == p.n) & (h.nnz == p.nnz) &
+           (h.rowptr_addr == p.rowptr_key);
 }
 
 __device__ __forceinline__ bool header_ok(const WsHeader *hdr, const AggParams &p)

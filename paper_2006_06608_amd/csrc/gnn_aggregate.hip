@@ -392,7 +392,10 @@ template <bool WEIGHTED>
 __global__ __launch_bounds__(256) void k_aggregate_noblock(AggParams p)
 {
     const WsHeader *hdr = p.hdr;
-    if (!header_ok(hdr, p)) return;
+    if (!header_ok(hdr, p)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) note_stale(p.hdr, p);
+        return;
+    }
     const int64_t num_ng = hdr->num_ng;
     const int dwl_log2 = p.dwl_log2, dwl = 1 << dwl_log2;
     const int lane = threadIdx.x & 63;
@@ -525,6 +528,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     p.ngs = ngs;
     p.dwl_log2 = dwl_log2;
     p.nnz = nnz;
+    p.rowptr_key = (uint64_t)(uintptr_t)rowptr;
     // runs of consecutive tiles per XCD: by default from ngs = 16 on (1-3 % faster on all five
     // configurations; with smaller groups it measured up to 15 % slower), always on request
     p.xcd_remap = ((flags & GNN_FLAG_XCD_RUNS) || ngs >= 16) ? 1 : 0;
@@ -596,10 +600,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
         while (wpb * (64 >> dwl_log2) < kPartMinTile && wpb < kMaxWavesPerBlock) wpb *= 2;
     const int T = wpb * (64 >> dwl_log2);
     p.T = T;
-    size_t lds = (size_t)(kMaxWavesPerBlock + T + (size_t)T * ngs * (weighted ? 2 : 1)) * 4;
-    lds = (lds + 15) & ~(size_t)15;
-    lds += (size_t)T * dim * 4;
-    lds += (size_t)wpb * 64 * 4;  // per-wave list of empty rows (appended blocks)
+    const size_t lds = agg_lds_bytes(T, ngs, dim, wpb, weighted);
     if (lds > kMaxLdsBytes) return GNN_ELIMIT;
 
     const int64_t tiles_upper = (ng_cap + T - 1) / T;

@@ -214,8 +214,8 @@ static void modularity_order(int32_t n, const int32_t *rowptr, const int32_t *co
 void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, int vec, int32_t *ngs, int32_t *dw,
                      int32_t *wpb)
 {
-    (void)max_degree;
     const double avg = n > 0 ? (double)nnz / (double)n : 0.0;
+    const bool auto_dw = *dw <= 0;
     // dimension workers: lanes per neighbor row.  Each lane moves `vec` floats per load and owns up
     // to 4 chunks of the row.  A lane should have about 8 independent loads in flight; a row of at
     // most 4 neighbors supplies them in one batch only if the lane takes two chunks (a two-chunk lane
@@ -223,9 +223,10 @@ void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, in
     // 5..8 neighbors would need a second batch and gain nothing).  Among the
     // admissible powers of two take the one that leaves the fewest lane slots idle
     // (dw * chunks - row length in vectors), and among equals the widest team (fewest chunks).
-    if (*dw <= 0) {
+    if (auto_dw) {
         const int units = (dim + vec - 1) / vec;
-        const int min_chunks = (avg <= 4.0 && units >= 2) ? 2 : 1;
+        const bool short_rows = avg <= 4.0;
+        const int min_chunks = (short_rows && units >= 2) ? 2 : 1;
         int best = 64, best_waste = 1 << 30;
         for (int d = 1; d <= 64; d *= 2) {
             const int chunks = (units + d - 1) / d;
@@ -243,17 +244,27 @@ void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, in
     // fewer tuples, reductions and flushes per entry, and a team needs at least the 8 rows it keeps
     // in flight; past about twice the mean row length most groups are a whole row and nothing
     // more is gained.  Measured knee on MI355X: 16..32, as the paper found on its GPUs (Sec. 7.4).
+    // A known longest row below that caps it: larger groups would only enlarge the index staging.
     if (*ngs <= 0) {
         int g = 16;
         while (g < 32 && (double)g < 2.0 * avg) g *= 2;
+        if (max_degree > 0)
+            while (g > 16 && g / 2 >= max_degree) g /= 2;
         *ngs = g;
     }
     // waves per block: 4 (the paper's preferred small blocks, Sec. 6), fewer when a wave already
-    // carries many teams, so that a block serves at most 64 neighbor groups
+    // carries many teams, so that a block serves at most 64 neighbor groups -- and Eq. 5's second
+    // constraint, re-derived: the block's scratch memory (slots of Dim floats per group plus the staged
+    // indices) must fit the per-block budget that keeps several blocks on a CU's 160 KB.  Fewer waves
+    // per block shrink it; if one wave is still too much and the team width is free, wider teams do.
     if (*wpb <= 0) {
         const int teams = 64 / (*dw > 0 ? *dw : 1);
         int w = 64 / teams;
-        *wpb = w < 1 ? 1 : (w > 4 ? 4 : w);
+        w = w < 1 ? 1 : (w > 4 ? 4 : w);
+        while (w > 1 && agg_lds_bytes(w * (64 / *dw), *ngs, dim, w, true) > kMaxLdsBytes) w /= 2;
+        if (auto_dw)
+            while (*dw < 64 && agg_lds_bytes(64 / *dw, *ngs, dim, 1, true) > kMaxLdsBytes) *dw *= 2;
+        *wpb = w;
     }
 }
 
@@ -372,7 +383,8 @@ int gnn_decide(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, int32_t 
                int32_t *waves_per_block)
 {
     if (n < 0 || nnz < 0 || dim <= 0 || !ngs || !dw || !waves_per_block) return GNN_EINVAL;
-    int32_t a = 0, b = 0, c = 0;
+    int32_t a = *ngs, b = *dw, c = *waves_per_block;
+    if (a < 0 || b < 0 || c < 0 || b > 64 || (b & (b - 1)) != 0 || c > kMaxWavesPerBlock) return GNN_EINVAL;
     const int vec = dim % 4 == 0 ? 4 : (dim % 2 == 0 ? 2 : 1);
     decide_defaults(n, nnz, max_degree, dim, vec, &a, &b, &c);
     *ngs = a;

@@ -97,6 +97,19 @@ inline size_t part_rows_bytes(int64_t ng_capacity, int tile, int32_t dim)
     return align_up(sizeof(float) * 2 * (size_t)(tiles > 0 ? tiles : 1) * (size_t)dim);
 }
 
+// LDS bytes of one block of the one-block-per-tile aggregation kernel: per-wave leader counts, one
+// "saw the node's last group" flag per group, the staged column indices (and weights) of the block's
+// T groups of up to ngs entries, one slot of dim floats per group (Algorithm 1), and a 64-entry list of
+// rows without entries per wave.  T = waves_per_block * 64 / dw.
+inline size_t agg_lds_bytes(int T, int32_t ngs, int32_t dim, int wpb, bool weighted)
+{
+    size_t b = (size_t)(kMaxWavesPerBlock + T + (size_t)T * ngs * (weighted ? 2 : 1)) * 4;
+    b = (b + 15) & ~(size_t)15;
+    b += (size_t)T * dim * 4;
+    b += (size_t)wpb * 64 * 4;
+    return b;
+}
+
 // Request to fuse the Update GEMM into a GIN aggregation (gnn_layer_forward); done tells the caller
 // whether the fused kernel was used.
 struct FuseSpec {

@@ -176,6 +176,37 @@ def test_config5_aggregation_for_every_group_size_of_the_sweep(ngs):
     assert_parity(run_gin(chain.G, 0.0, X, ngs=ngs), ref, ab, f"config 5 aggregation ngs {ngs}")
 
 
+def test_config5_renumbered_at_full_size_gives_the_same_aggregation():
+    """Sec. 5.1: renumbering must not change the result.  The largest graph at full size: the library's
+    permutation and relabelled CSR equal the oracle's byte for byte, and the GIN aggregation of the
+    renumbered graph, rows moved back, equals the oracle's aggregation of the original graph."""
+    g = config_graph(5)
+    X = features(g.n, 64, BASE_SEED + 5)
+    perm, iperm, _, did = gnn.gnn_reorder(g.rowptr, g.colidx)
+    assert did  # Eq. 4 of the scrambled ids is far above the rule's threshold
+    operm, oiperm = oracle.reorder(g.rowptr, g.colidx)
+    assert perm.tobytes() == operm.tobytes() and iperm.tobytes() == oiperm.tobytes()
+    rp2, ci2 = gnn.gnn_apply_perm_csr(g.rowptr, g.colidx, perm)
+    orp, oci = oracle.apply_perm_csr(g.rowptr, g.colidx, operm)
+    assert rp2.tobytes() == orp.tobytes() and ci2.tobytes() == oci.tobytes()
+    G2 = DeviceGraph(rp2, ci2)
+    Xp = torch.empty(g.n, 64, device="cuda")
+    gnn.gnn_permute_rows(g.n, 64, dev(perm), dev(X), Xp)
+    assert np.array_equal(Xp.cpu().numpy(), oracle.permute_rows(X, perm))
+    out2 = torch.full((g.n, 64), float("nan"), device="cuda")
+    ws = gnn.alloc_workspace(G2.n, G2.nnz, 64, 0)
+    gnn.gnn_aggregate_gin(G2.n, G2.nnz, G2.rowptr, G2.colidx, 0.0, Xp, out2, 64, 0, 0, 0, 0, ws)
+    back = torch.empty_like(out2)
+    gnn.gnn_permute_rows(g.n, 64, dev(iperm), out2, back)  # row perm[i] of the renumbered result is node i
+    torch.cuda.synchronize()
+    gnn.gnn_workspace_status(ws)
+    key = ("cfg5", "agg_ref")
+    if key not in _chains:
+        _chains[key] = oracle.aggregate_gin(g.rowptr, g.colidx, 0.0, X, want_abs=True)
+    ref, ab = _chains[key]
+    assert_parity(back.cpu().numpy(), ref, ab, "config 5 renumbered, rows moved back")
+
+
 # ------------------------------------------------------------------ whole model in one call
 @pytest.mark.parametrize("cfg,shrink", [(2, 4), (3, 8), (4, 32)])
 def test_model_forward_equals_the_layer_by_layer_chain_and_the_oracle(cfg, shrink):

@@ -79,13 +79,19 @@ def test_reorder_hand_trace_and_rule():
     assert did3 and np.array_equal(perm3, oracle.reorder(rp2, ci2)[0])
 
 
-@pytest.mark.parametrize("cfg,shrink", [(1, 1), (2, 1), (3, 1), (4, 16), (5, 16)])
+@pytest.mark.parametrize("cfg,shrink", [(1, 1), (2, 1), (3, 1), (4, 1), (5, 1), (4, 16), (5, 16)])
 def test_reorder_matches_oracle_bitwise(cfg, shrink):
+    """All five configurations at full size (the oracle takes about 3 s on the largest), and two reduced ones."""
     g = config_graph(cfg, shrink=shrink)
     perm, iperm, aes, did = gnn.gnn_reorder(g.rowptr, g.colidx, force=True)
     operm, oiperm = oracle.reorder(g.rowptr, g.colidx)
     assert perm.tobytes() == operm.tobytes()
     assert iperm.tobytes() == oiperm.tobytes()
+    assert np.array_equal(np.sort(perm), np.arange(g.n, dtype=np.int32)) and np.array_equal(iperm[perm], np.arange(g.n))
+    if shrink == 1:
+        rp2, ci2 = gnn.gnn_apply_perm_csr(g.rowptr, g.colidx, perm)
+        orp, oci = oracle.apply_perm_csr(g.rowptr, g.colidx, operm)
+        assert rp2.tobytes() == orp.tobytes() and ci2.tobytes() == oci.tobytes()
     s, a = gnn.gnn_aes(g.rowptr, g.colidx)
     assert s == oracle.aes_sum(g.rowptr, g.colidx) and a == aes
     _, _, _, did_rule = gnn.gnn_reorder(g.rowptr, g.colidx)
@@ -131,3 +137,33 @@ def test_paper_model_literal_and_decide_ranges():
         ngs, dw, wpb = gnn.gnn_decide(n, nnz, 0, dim)
         assert 1 <= ngs <= 64 and 1 <= wpb <= 16
         assert 1 <= dw <= 64 and dw & (dw - 1) == 0
+
+
+def test_the_models_own_choice_always_fits_the_scratch_memory_of_a_block():
+    """Eq. 5's second constraint re-derived: whatever the graph and the row width (up to 15,000 floats),
+    the automatic (ngs, dw, waves per block) need at most 64 KB of scratch memory per block (formula of
+    gnn.h), also when the caller fixes one or two of the three."""
+    rng = np.random.default_rng(0)
+
+    def need(dim, ngs, dw, wpb):
+        T = wpb * (64 // dw)
+        return -(-4 * (16 + T + 2 * T * ngs) // 16) * 16 + 4 * T * dim + 256 * wpb
+
+    dims = list(range(1, 70)) + [96, 100, 128, 200, 256, 500, 512, 1000, 1024, 1433, 2048, 3703, 4096, 8192, 12000, 15000]
+    for dim in dims:
+        for _ in range(6):
+            n = int(rng.integers(1, 2_000_000))
+            nnz = int(n * rng.choice([0.0, 0.5, 3.7, 15.0, 60.0, 500.0]))
+            ngs, dw, wpb = gnn.gnn_decide(n, nnz, int(rng.choice([0, 3, 40, 100000])), dim)
+            assert 1 <= ngs <= 64 and 1 <= wpb <= 16 and dw in (1, 2, 4, 8, 16, 32, 64)
+            assert need(dim, ngs, dw, wpb) <= 65536, (dim, n, nnz, ngs, dw, wpb)
+            # the caller fixes the group size (a sweep): the rest still fits
+            ngs2 = int(rng.choice([1, 2, 4, 8, 16, 32, 64]))
+            g2, dw2, wpb2 = gnn.gnn_decide(n, nnz, 0, dim, ngs=ngs2)
+            assert g2 == ngs2 and need(dim, g2, dw2, wpb2) <= 65536, (dim, n, nnz, g2, dw2, wpb2)
+    # a caller's own values are kept, bad ones refused
+    assert gnn.gnn_decide(1000, 5000, 0, 64, 8, 4, 2) == (8, 4, 2)
+    with pytest.raises(gnn.GnnError):
+        gnn.gnn_decide(1000, 5000, 0, 64, dw=3)
+    with pytest.raises(gnn.GnnError):
+        gnn.gnn_decide(1000, 5000, 0, 64, waves_per_block=17)
