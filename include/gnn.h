@@ -244,16 +244,6 @@ int gnn_layer_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, c
                       int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
                       void *stream);
 
-/* gnn_layer_forward with two timing taps: ev_agg_start / ev_agg_stop (hipEvent_t, either may be
- * NULL) are recorded on `stream` immediately before and after the main aggregation kernel of
- * the layer, so that a benchmark can time that kernel inside a running model without a
- * profiler.  Everything else is identical to gnn_layer_forward. */
-int gnn_layer_forward_timed(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
-                            const float *ew, float eps, const float *X, int32_t in_dim, const float *W,
-                            const float *b, int32_t out_dim, int relu, float *out, int32_t ngs, int32_t dw,
-                            int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
-                            void *stream, void *ev_agg_start, void *ev_agg_stop);
-
 /* A whole model in one call (the evaluation settings of Sec. 7.1: GCN 2 layers, GIN 5 layers):
  * num_layers calls of gnn_layer_forward chained, ReLU after every layer but the last, the neighbor
  * partition built once (or reused with GNN_FLAG_REUSE_PARTITION).  dims: HOST int32[num_layers+1],
@@ -326,19 +316,6 @@ int gnn_aes_device(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t 
 /* Row gather for renumbering: Y[perm[i],:] = X[i,:] (pass iperm to undo).  DEVICE pointers,
  * perm int32[n]. */
 int gnn_permute_rows(int32_t n, int32_t dim, const int32_t *perm, const float *X, float *Y, void *stream);
-
-/* ---- measuring kernels -------------------------------------------------------------- */
-/* What the memory system delivers, for a benchmark to quote beside the published peak (the roofline
- * of the aggregation, Sec. 7 of the paper reports its bandwidth the same way).  Both only enqueue a
- * kernel; the caller times it.  sink: DEVICE float[1], never written for finite data.
- * gnn_bench_stream_read: reads `bytes` (16-byte aligned src) once, sequentially.
- * gnn_bench_gather_rows: teams of lanes read the rows idx[0..nidx) of X[n, dim] with 16-byte
- * loads, eight rows in flight per team (the aggregation kernel's loads without its tuples, reduction
- * and stores); dim = 4 x (a power of two up to 64) x (1..4), e.g. 16, 64, 96, 256; 0 <= idx[k] < n is the
- * caller's duty; nidx is rounded down to a multiple of 8. */
-int gnn_bench_stream_read(const void *src, size_t bytes, float *sink, void *stream);
-int gnn_bench_gather_rows(int32_t n, int32_t dim, const float *X, const int32_t *idx, int64_t nidx, float *sink,
-                          void *stream);
 
 /* ---- diagnostics ------------------------------------------------------------------ */
 const char *gnn_strerror(int code);

@@ -285,6 +285,83 @@ def gin_model(rowptr, colidx, eps, X, Ws: Sequence[np.ndarray], bs: Optional[Seq
     return (H, ab) if want_abs else H
 
 
+# ------------------------------------------------------------------ the same loops on several cores
+# For the benchmark's all-cores baseline only.  Rows of an aggregation and of the dense layer are
+# independent, so disjoint row ranges (balanced by their number of entries) of the very same C loops
+# are handed to threads (ctypes releases the interpreter lock during a call).  Results equal the
+# single-thread functions bit for bit (tests/test_oracle_layers.py).
+def _row_ranges(rowptr, parts: int):
+    n = rowptr.size - 1
+    cost = rowptr.astype(np.int64) + np.arange(n + 1, dtype=np.int64)  # entries + one unit per row
+    cuts = np.searchsorted(cost, np.linspace(0, cost[-1], parts + 1)[1:-1])
+    edges = [0] + [int(c) for c in cuts] + [n]
+    return [(a, b) for a, b in zip(edges[:-1], edges[1:]) if b > a]
+
+
+def _run_threads(fn, ranges, threads):
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(lambda r: fn(*r), ranges))
+
+
+def _off(a: np.ndarray, row: int):
+    return ctypes.c_void_p(a.ctypes.data + row * a.strides[0])
+
+
+def gin_layer_threads(rowptr, colidx, eps, X, W, b, relu: bool, threads: int):
+    rowptr, colidx, X, W = _i32(rowptr), _i32(colidx), _f32(X), _f32(W)
+    b = None if b is None else _f32(b)
+    n, K, M = rowptr.size - 1, X.shape[1], W.shape[1]
+    A = np.empty((n, K), dtype=np.float32)
+    out = np.empty((n, M), dtype=np.float32)
+    L = _L()
+
+    def work(r0, r1):
+        L.orc_aggregate_gin_rows(ctypes.c_int32(r0), ctypes.c_int32(r1), _p(rowptr), _p(colidx), ctypes.c_float(eps),
+                                 _p(X), ctypes.c_int32(K), _p(A), None)
+        L.orc_gemm_bias_act(ctypes.c_int32(r1 - r0), ctypes.c_int32(K), ctypes.c_int32(M), _off(A, r0), _p(W), _p(b),
+                            ctypes.c_int32(1 if relu else 0), _off(out, r0), None)
+
+    _run_threads(work, _row_ranges(rowptr, 4 * threads), threads)
+    return out
+
+
+def gcn_layer_threads(rowptr, colidx, ew, X, W, b, relu: bool, threads: int):
+    rowptr, colidx, X, W = _i32(rowptr), _i32(colidx), _f32(X), _f32(W)
+    ew = None if ew is None else _f32(ew)
+    b = None if b is None else _f32(b)
+    n, K, M = rowptr.size - 1, X.shape[1], W.shape[1]
+    H = np.empty((n, M), dtype=np.float32)
+    Z = np.empty((n, M), dtype=np.float32)
+    out = np.empty((n, M), dtype=np.float32)
+    L = _L()
+    ranges = _row_ranges(rowptr, 4 * threads)
+    _run_threads(lambda r0, r1: L.orc_gemm_bias_act(ctypes.c_int32(r1 - r0), ctypes.c_int32(K), ctypes.c_int32(M),
+                                                    _off(X, r0), _p(W), None, ctypes.c_int32(0), _off(H, r0), None),
+                 ranges, threads)
+
+    def work(r0, r1):  # rowptr + r0 keeps absolute positions, so colidx and ew are passed whole
+        L.orc_aggregate_gcn(ctypes.c_int32(r1 - r0), _off(rowptr, r0), _p(colidx), _p(ew), _p(H), ctypes.c_int32(M),
+                            _off(Z, r0), None)
+        L.orc_bias_act(ctypes.c_int32(r1 - r0), ctypes.c_int32(M), _off(Z, r0), _p(b), ctypes.c_int32(1 if relu else 0),
+                       _off(out, r0))
+
+    _run_threads(work, ranges, threads)
+    return out
+
+
+def aggregate_gcn_threads(rowptr, colidx, ew, X, threads: int):
+    rowptr, colidx, X = _i32(rowptr), _i32(colidx), _f32(X)
+    ew = None if ew is None else _f32(ew)
+    n, dim = rowptr.size - 1, X.shape[1]
+    out = np.empty((n, dim), dtype=np.float32)
+    L = _L()
+    _run_threads(lambda r0, r1: L.orc_aggregate_gcn(ctypes.c_int32(r1 - r0), _off(rowptr, r0), _p(colidx), _p(ew), _p(X),
+                                                    ctypes.c_int32(dim), _off(out, r0), None),
+                 _row_ranges(rowptr, 4 * threads), threads)
+    return out
+
+
 # ------------------------------------------------------------------ backward pass (training)
 # Gradients of the layers above, by the chain rule, each product accumulated in double and stored
 # as float between operations (as the forward pass does).  The aggregation of gradients runs over

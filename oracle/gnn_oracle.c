@@ -92,10 +92,10 @@ void orc_aggregate_f64(int32_t n, const int32_t *rowptr, const int32_t *colidx, 
 
 /* ------------------------------------------------------------------ Eq. 3: GIN aggregation
  * out[i,:] = (1 + eps) * X[i,:] + sum_{j in N(i)} X[j,:]   (the argument of h in Eq. 3). */
-void orc_aggregate_gin(int32_t n, const int32_t *rowptr, const int32_t *colidx, float eps,
-                       const float *X, int32_t dim, float *out, double *abs_out)
+void orc_aggregate_gin_rows(int32_t row_begin, int32_t row_end, const int32_t *rowptr, const int32_t *colidx,
+                            float eps, const float *X, int32_t dim, float *out, double *abs_out)
 {
-    for (int32_t i = 0; i < n; ++i) {
+    for (int32_t i = row_begin; i < row_end; ++i) {
         for (int32_t k = 0; k < dim; ++k) {
             double self = (1.0 + (double)eps) * (double)X[(size_t)i * dim + k];
             double acc = self, aacc = fabs(self);
@@ -108,6 +108,14 @@ void orc_aggregate_gin(int32_t n, const int32_t *rowptr, const int32_t *colidx, 
             if (abs_out) abs_out[(size_t)i * dim + k] = aacc;
         }
     }
+}
+
+/* All rows.  (The row-range form above exists so that the benchmark's all-cores baseline can hand
+ * disjoint row ranges of the same loop to several threads; rows are independent.) */
+void orc_aggregate_gin(int32_t n, const int32_t *rowptr, const int32_t *colidx, float eps,
+                       const float *X, int32_t dim, float *out, double *abs_out)
+{
+    orc_aggregate_gin_rows(0, n, rowptr, colidx, eps, X, dim, out, abs_out);
 }
 
 /* ------------------------------------------------------------------ Sec. 3.1: other neighbour aggregations

@@ -34,7 +34,7 @@ GNN_REDUCE_SUM, GNN_REDUCE_MAX, GNN_REDUCE_MIN, GNN_REDUCE_MEAN = 0, 1, 2, 3
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("GNN_MI355X_LIB") or os.path.join(_PKG, "libgnn_mi355x.so")
 
-# every symbol include/gnn.h declares
+# every symbol include/gnn.h and include/gnn_bench.h declare
 _SYMBOLS = [
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",

@@ -3,6 +3,7 @@
 // bare gather of feature rows (the aggregation kernel's loads without tuples, reduction or stores).
 #include <hip/hip_runtime.h>
 
+#include "gnn_bench.h"
 #include "gnn_internal.h"
 
 namespace gnn {

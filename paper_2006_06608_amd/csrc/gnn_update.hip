@@ -8,6 +8,7 @@
 // register prefetch of the next K chunk while the current one is multiplied).
 #include <hip/hip_runtime.h>
 
+#include "gnn_bench.h"
 #include "gnn_launch.h"
 
 namespace gnn {

@@ -16,8 +16,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "gnn.h")).read()
-    declared = set(re.findall(r"\b(gnn_[a-z0-9_]+)\s*\(", header))
+    import glob
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert [os.path.basename(h) for h in headers] == ["gnn.h", "gnn_bench.h"]
+    declared = set()
+    for h in headers:
+        declared |= set(re.findall(r"\b(gnn_[a-z0-9_]+)\s*\(", open(h).read()))
     assert declared, "no declarations found"
     lib = gnn.load()
     for name in declared:
@@ -32,9 +36,10 @@ def test_header_is_plain_c():
     import subprocess
     if shutil.which("gcc") is None:
         pytest.skip("needs gcc")
-    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
-                        os.path.join(ROOT, "include", "gnn.h")], capture_output=True, text=True)
-    assert r.returncode == 0, r.stderr
+    for h in ("gnn.h", "gnn_bench.h"):
+        r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                            os.path.join(ROOT, "include", h)], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
 
 
 def test_host_argument_validation():

@@ -210,3 +210,25 @@ def test_aggregation_error_scales_are_the_sums_of_absolute_terms():
     b = rng.standard_normal(4).astype(np.float32)
     _, ab = oracle.gemm_bias_act(A, W, b, True, want_abs=True)
     np.testing.assert_allclose(ab, np.abs(_f64(A)) @ np.abs(_f64(W)) + np.abs(_f64(b)), rtol=1e-12)
+
+
+def test_row_partitioned_forms_equal_the_single_thread_functions_bit_for_bit():
+    """The benchmark's all-cores baseline runs the same C loops on disjoint row ranges."""
+    from gnn_synth import config_graph, features, glorot
+    g = config_graph(2, shrink=4)
+    X = features(g.n, 24, seed=1)
+    W = glorot(24, 10, seed=2)
+    b = features(1, 10, seed=3)[0]
+    ew = oracle.gcn_norm(g.rowptr, g.colidx)
+    for threads in (1, 3, 8):
+        assert np.array_equal(oracle.gcn_layer_threads(g.rowptr, g.colidx, ew, X, W, b, True, threads),
+                              oracle.gcn_layer(g.rowptr, g.colidx, ew, X, W, b, True))
+        assert np.array_equal(oracle.gin_layer_threads(g.rowptr, g.colidx, 0.5, X, W, b, True, threads),
+                              oracle.gin_layer(g.rowptr, g.colidx, 0.5, X, W, b, True))
+        assert np.array_equal(oracle.aggregate_gcn_threads(g.rowptr, g.colidx, ew, X, threads),
+                              oracle.aggregate_gcn(g.rowptr, g.colidx, ew, X))
+    g5 = config_graph(5, shrink=64)  # many rows without entries
+    X5 = features(g5.n, 8, seed=4)
+    W5 = glorot(8, 8, seed=5)
+    assert np.array_equal(oracle.gin_layer_threads(g5.rowptr, g5.colidx, 0.0, X5, W5, None, False, 5),
+                          oracle.gin_layer(g5.rowptr, g5.colidx, 0.0, X5, W5, None, False))
