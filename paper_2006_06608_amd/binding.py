@@ -13,7 +13,7 @@ __all__ = [
     "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_FLAG_NO_FUSION", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
     "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall", "AggregateCall",
     "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
-    "gnn_bench_stream_read", "gnn_bench_gather_rows", "gnn_csr_transpose_device",
+    "gnn_bench_stream_read", "gnn_bench_gather_rows", "gnn_csr_transpose_device", "gnn_bench_last_aggregation",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
@@ -43,7 +43,7 @@ _SYMBOLS = [
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
     "gnn_last_hip_error", "gnn_version", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
     "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
-    "gnn_bench_stream_read", "gnn_bench_gather_rows", "gnn_csr_transpose_device",
+    "gnn_bench_stream_read", "gnn_bench_gather_rows", "gnn_csr_transpose_device", "gnn_bench_last_aggregation",
 ]
 
 
@@ -285,6 +285,12 @@ def gnn_aggregate_gin(n, nnz, rowptr, colidx, eps, X, out, dim, ngs=0, dw=0, wav
                                   _f32(eps), _dev(X, "float32", "X"), _dev(out, "float32", "out"), _i32(dim),
                                   _i32(ngs), _i32(dw), _i32(waves_per_block), _u32(flags), wp, wb, _stream(stream))
     _check(rc, "gnn_aggregate_gin")
+
+
+def gnn_bench_last_aggregation() -> str:
+    buf = ctypes.create_string_buffer(256)
+    _check(load().gnn_bench_last_aggregation(buf, _sz(256)), "gnn_bench_last_aggregation")
+    return buf.value.decode()
 
 
 class AggregateCall:

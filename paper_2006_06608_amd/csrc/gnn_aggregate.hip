@@ -26,6 +26,9 @@
 // own-row term enters the sum with the first group of each node.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+
+#include "gnn_bench.h"
 #include "gnn_launch.h"
 
 namespace gnn {
@@ -452,6 +455,30 @@ static void launch_main(int op, bool weighted, bool self, dim3 grid, dim3 block,
     else hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, false, kOpSum>), grid, block, lds, s, p);
 }
 
+// ---- what the calling thread launched last (gnn_bench_last_aggregation) ----
+struct LastLaunch {
+    const char *kernel;
+    int vec, iter, u, weighted, self, op, T, ngs, wpb, ordered, xcd;
+};
+static thread_local LastLaunch g_last = {"none", 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+void note_launch(const char *kernel, int vec, int iter, int u, bool weighted, bool self, int op, int T, int ngs, int wpb,
+                 bool ordered, bool xcd)
+{
+    g_last = LastLaunch{kernel, vec, iter, u, weighted ? 1 : 0, self ? 1 : 0, op, T, ngs, wpb, ordered ? 1 : 0, xcd ? 1 : 0};
+}
+
+// U of launch_vec below, for the launch description
+static int unroll_of(int vec, int iter)
+{
+    switch (iter) {
+        case 1: return 8;
+        case 2: return vec == 4 ? 4 : 8;
+        case 3: return 4;
+        default: return vec == 4 ? 2 : 4;
+    }
+}
+
 template <int VEC>
 static void launch_vec(int op, int iter, bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s,
                        const AggParams &p)
@@ -554,6 +581,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
             else hipLaunchKernelGGL(k_aggregate_noblock<false>, dim3((unsigned)blocks), dim3(256), 0, s, p);
         }
         if (bias || relu) hipLaunchKernelGGL(k_epilogue_all, dim3(2048), dim3(256), 0, s, p);
+        note_launch("k_aggregate_noblock", 1, 1, 1, weighted, self, op, 1, ngs, 4, false, false);
         GNN_HIP_TRY(hipGetLastError());
         return GNN_OK;
     }
@@ -584,6 +612,9 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
                                                 (ng_cap + pf.T - 1) / pf.T, s);
             if (rc < 0) return rc;
             if (rc == GNN_OK) {
+                const int it_f = p.iter_total < 4 ? p.iter_total : 4;
+                note_launch("k_gin_layer_fused", vec, it_f, unroll_of(vec, it_f), false, true, op, pf.T, ngs, wpb_f, true,
+                            p.xcd_remap != 0);
                 if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
                 fuse->done = true;
                 GNN_HIP_TRY(hipGetLastError());
@@ -636,6 +667,8 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
             if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
             const int rc = launch_aggregate_pipe(vec, iter, weighted, self, blocks, wpb, plds, s, p);
             if (rc != GNN_OK) return rc;
+            note_launch("k_aggregate_pipe", vec, iter, unroll_of(vec, iter), weighted, self, op, T, ngs, wpb, false,
+                        p.xcd_remap != 0);
             if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
             if (bias || relu)
                 hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
@@ -667,6 +700,8 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
         else if (vec == 2) launch_vec<2>(op, iter, weighted, self, g, b, lds, s, p);
         else launch_vec<1>(op, iter, weighted, self, g, b, lds, s, p);
     }
+    note_launch("k_aggregate", vec, iter, unroll_of(vec, iter), weighted && op == kOpSum, self && op == kOpSum, op, T, ngs,
+                wpb, ordered, p.xcd_remap != 0);
     if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
     if (!ordered && (bias || relu))
         hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)init_blocks), dim3(256), 0, s, p);
@@ -679,6 +714,16 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
 using namespace gnn;
 
 extern "C" {
+
+int gnn_bench_last_aggregation(char *buf, size_t cap)
+{
+    if (!buf || cap == 0) return GNN_EINVAL;
+    const LastLaunch &l = g_last;
+    const int k = snprintf(buf, cap, "%s<%d,%d,%d,%s,%s,%d> groups/block=%d ngs=%d waves/block=%d flush=%s tiles=%s",
+                           l.kernel, l.vec, l.iter, l.u, l.weighted ? "true" : "false", l.self ? "true" : "false", l.op,
+                           l.T, l.ngs, l.wpb, l.ordered ? "ordered" : "atomic", l.xcd ? "xcd-runs" : "round-robin");
+    return (k < 0 || (size_t)k >= cap) ? GNN_ELIMIT : GNN_OK;
+}
 
 int gnn_aggregate_gcn(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *ew,
                       const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t waves_per_block,

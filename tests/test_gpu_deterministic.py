@@ -164,3 +164,40 @@ def test_ordered_flush_on_two_streams_at_once():
         assert torch.equal(oa, ref_a) and torch.equal(ob, ref_b)
     gnn.gnn_workspace_status(wsa)
     gnn.gnn_workspace_status(wsb)
+
+
+@pytest.mark.parametrize("dim,dw", [(64, 16), (16, 4), (96, 8), (7, 8)])
+def test_every_node_spans_many_blocks_and_integer_sums_are_exact(dim, dw):
+    """Sharp test of the cross-block hand-over of the ordered flush.  With one entry per group and one
+    wave per block, a block serves 64/dw groups, so every node of this dense graph (rows of 128 to 223
+    entries) spans at least eight blocks, which the dispatcher deals over all XCDs: every output row is
+    the sum of partial rows published by other blocks.  Features and weights are small integers, so every
+    partial sum is exact in fp32 and the result must equal the oracle bit for bit: a stale or torn partial
+    row cannot hide in rounding."""
+    rng = np.random.default_rng(77)
+    n = 256
+    rows = [np.sort(rng.choice(n, size=int(rng.integers(128, 224)), replace=False)) for _ in range(n)]
+    rp = np.concatenate([[0], np.cumsum([r.size for r in rows])]).astype(np.int32)
+    ci = np.concatenate(rows).astype(np.int32)
+    per_block = 64 // dw
+    assert min(r.size for r in rows) >= 8 * per_block
+    X = rng.integers(-8, 9, size=(n, dim)).astype(np.float32)
+    ew = rng.integers(1, 4, size=ci.size).astype(np.float32)
+    G, Gw = DeviceGraph(rp, ci), DeviceGraph(rp, ci, ew)
+    ref_gin = oracle.aggregate_gin(rp, ci, 1.0, X)       # (1 + eps) = 2: still integers
+    ref_gcn = oracle.aggregate_gcn(rp, ci, ew, X)
+    ws = gnn.alloc_workspace(n, ci.size, dim, 1)
+    for rep in range(20):
+        got = run_gin(G, 1.0, X, ngs=1, dw=dw, wpb=1, flags=DET, ws=ws)
+        assert np.array_equal(got.view(np.uint32), ref_gin.view(np.uint32)), f"GIN, repetition {rep}"
+        got = run_gcn(Gw, X, ngs=1, dw=dw, wpb=1, flags=DET, ws=ws)
+        assert np.array_equal(got.view(np.uint32), ref_gcn.view(np.uint32)), f"GCN, repetition {rep}"
+    # the same with a few hubs that span thousands of blocks
+    star_rp, star_ci = csr_from_edges(6001, [(h, i) for h in (0, 1, 2) for i in range(3, 6001)], self_loops=True)
+    Xs = rng.integers(-3, 4, size=(6001, dim)).astype(np.float32)
+    Gs = DeviceGraph(star_rp, star_ci)
+    ref = oracle.aggregate_gin(star_rp, star_ci, 0.0, Xs)
+    wss = gnn.alloc_workspace(6001, star_ci.size, dim, 1)
+    for rep in range(5):
+        got = run_gin(Gs, 0.0, Xs, ngs=1, dw=dw, wpb=1, flags=DET, ws=wss)
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), f"hubs, repetition {rep}"
