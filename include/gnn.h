@@ -212,6 +212,24 @@ int gnn_aggregate_gin(int32_t n, int64_t nnz, const int32_t *rowptr, const int32
                       int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
                       void *stream);
 
+/* gnn_aggregate_gin for callers that cannot allocate device memory or bring a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same
+ * kernels, same arguments, but the neighbor partition, the arrival counters and the partial rows of
+ * the ordered flush live in a fixed array of 128 MiB of device memory inside the library (one per GPU,
+ * held until the process ends) instead of a caller's workspace.  The call allocates nothing.
+ *   Limit: gnn_workspace_bytes(n, nnz, dim, ngs) must not exceed 128 MiB (ngs = 0: the model's choice;
+ *   e.g. 1 M nodes / 16 M entries at dim 64 need 81 MB), else GNN_ELIMIT and nothing is enqueued.
+ *   Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
+ *   threads) race; calls on one stream are ordered.  The array keeps the last call's partition, so
+ *   GNN_FLAG_REUSE_PARTITION is honoured for a repeated (rowptr, n, nnz, ngs) and reports GNN_ESTALE
+ *   otherwise; without the flag the partition is built (and the counters cleared) by kernels of this call.
+ *   scratch_out (HOST, may be NULL) receives the DEVICE address of the array, for gnn_workspace_status
+ *   and gnn_partition_export.
+ * Errors: as gnn_aggregate_gin, and GNN_ELIMIT as above. */
+int gnn_aggregate_gin_static(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, float eps,
+                             const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw,
+                             int32_t waves_per_block, uint32_t flags, void *stream, void **scratch_out);
+
 /* Aggregation over the neighbour embeddings alone with another reduction (Sec. 3.1 names sum and
  * min as examples): out[i,:] = reduce over the stored entries j of row i of X[j,:], no weights, no
  * self term.  op: GNN_REDUCE_SUM, GNN_REDUCE_MAX, GNN_REDUCE_MIN (elementwise, exact) or

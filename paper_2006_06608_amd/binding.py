@@ -16,7 +16,7 @@ __all__ = [
     "gnn_bench_stream_read", "gnn_bench_gather_rows", "gnn_csr_transpose_device", "gnn_bench_last_aggregation",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
-    "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
+    "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin", "gnn_aggregate_gin_static",
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
     "gnn_version", "alloc_workspace", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
 ]
@@ -38,7 +38,7 @@ _LIB_PATH = os.environ.get("GNN_MI355X_LIB") or os.path.join(_PKG, "libgnn_mi355
 _SYMBOLS = [
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
-    "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin",
+    "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin", "gnn_aggregate_gin_static",
     "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward",
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
     "gnn_last_hip_error", "gnn_version", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
@@ -103,6 +103,8 @@ def _dev(t, dtype_name: str, name: str):
     """Device pointer of a contiguous CUDA/HIP torch tensor (None -> NULL)."""
     if t is None:
         return None
+    if isinstance(t, int):  # a raw device address (the static scratch array of gnn_aggregate_gin_static)
+        return ctypes.c_void_p(t)
     import torch
     want = {"int32": torch.int32, "float32": torch.float32, "uint8": torch.uint8}[dtype_name]
     if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != want or not t.is_contiguous():
@@ -285,6 +287,19 @@ def gnn_aggregate_gin(n, nnz, rowptr, colidx, eps, X, out, dim, ngs=0, dw=0, wav
                                   _f32(eps), _dev(X, "float32", "X"), _dev(out, "float32", "out"), _i32(dim),
                                   _i32(ngs), _i32(dw), _i32(waves_per_block), _u32(flags), wp, wb, _stream(stream))
     _check(rc, "gnn_aggregate_gin")
+
+
+def gnn_aggregate_gin_static(n, nnz, rowptr, colidx, eps, X, out, dim, ngs=0, dw=0, waves_per_block=0, flags=0,
+                             stream=None) -> int:
+    """gnn_aggregate_gin on the library's own scratch array (no workspace, nothing allocated); returns the
+    device address of that array (accepted by gnn_workspace_status and gnn_partition_export)."""
+    addr = ctypes.c_void_p(0)
+    rc = load().gnn_aggregate_gin_static(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"),
+                                         _dev(colidx, "int32", "colidx"), _f32(eps), _dev(X, "float32", "X"),
+                                         _dev(out, "float32", "out"), _i32(dim), _i32(ngs), _i32(dw),
+                                         _i32(waves_per_block), _u32(flags), _stream(stream), ctypes.byref(addr))
+    _check(rc, "gnn_aggregate_gin_static")
+    return int(addr.value or 0)
 
 
 def gnn_bench_last_aggregation() -> str:

@@ -27,6 +27,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <mutex>
 
 #include "gnn_bench.h"
 #include "gnn_launch.h"
@@ -709,6 +710,32 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     return GNN_OK;
 }
 
+// ---- scratch memory of gnn_aggregate_gin_static: one array per GPU, held until the process ends ----
+constexpr size_t kStaticScratchBytes = (size_t)128 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, looked up once per GPU
+
+// Device address of the current GPU's copy of `scratch` (in host code the array's name is only a
+// stand-in: it must never be passed to a kernel or a memset).
+static int static_scratch(void **ptr)
+{
+    int dev = 0;
+    GNN_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return GNN_ELIMIT;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        GNN_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return GNN_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return GNN_OK;
+}
+
 }  // namespace gnn
 
 using namespace gnn;
@@ -723,6 +750,27 @@ int gnn_bench_last_aggregation(char *buf, size_t cap)
                            l.kernel, l.vec, l.iter, l.u, l.weighted ? "true" : "false", l.self ? "true" : "false", l.op,
                            l.T, l.ngs, l.wpb, l.ordered ? "ordered" : "atomic", l.xcd ? "xcd-runs" : "round-robin");
     return (k < 0 || (size_t)k >= cap) ? GNN_ELIMIT : GNN_OK;
+}
+
+int gnn_aggregate_gin_static(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, float eps,
+                             const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t waves_per_block,
+                             uint32_t flags, void *stream, void **scratch_out)
+{
+    if (n < 0 || nnz < 0 || dim <= 0 || ngs < 0) return GNN_EINVAL;
+    // the same layout gnn_workspace_bytes sizes for max_dim = dim (room for the ordered flush), with the
+    // group size the call will use
+    int32_t r_ngs = ngs, r_dw = dw > 0 && dw <= 64 && (dw & (dw - 1)) == 0 ? dw : 0, r_wpb = 0;
+    decide_defaults(n, nnz, 0, dim, 1, &r_ngs, &r_dw, &r_wpb);
+    const WsLayout L = ws_layout(n, nnz, 0, r_ngs);
+    const size_t need = L.total + part_rows_bytes(L.ng_capacity, kPartMinTile, dim);
+    if (need > kStaticScratchBytes) return GNN_ELIMIT;
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != GNN_OK) return rc;
+    if (scratch_out) *scratch_out = ws;
+    return aggregate_impl(true, 1.0f + eps, n, nnz, rowptr, colidx, nullptr, X, out, dim, ngs, dw, waves_per_block,
+                          flags, nullptr, 0, ws, kStaticScratchBytes, 0, (hipStream_t)stream, nullptr, nullptr,
+                          nullptr);
 }
 
 int gnn_aggregate_gcn(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *ew,
