@@ -198,7 +198,7 @@ int gnn_validate_csr_device(int32_t n, int64_t nnz, const int32_t *rowptr, const
  *   waves_per_block  1..16, 0 = model's choice (the paper's user-chosen threads-per-block / 64)
  * Errors: GNN_EINVAL, GNN_EWORKSPACE, GNN_EHIP, and GNN_ELIMIT when a block's scratch memory would
  * exceed 64 KB: with T = waves_per_block * 64 / dw groups per block the need is
- *   round_up_16(4 * (16 + T + T * ngs * (ew ? 2 : 1))) + 4 * T * dim + 256 * waves_per_block  bytes
+ *   round_up_16(4 * (T * ngs + 8) * (ew ? 2 : 1)) + 4 * waves_per_block * dim + 128 + 256 * waves_per_block  bytes
  * (the model's own choices never exceed it; caller-chosen ngs / dw / waves_per_block can). */
 int gnn_aggregate_gcn(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
                       const float *ew, const float *X, float *out, int32_t dim, int32_t ngs,

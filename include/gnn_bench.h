@@ -38,7 +38,7 @@ int gnn_bench_gather_rows(int32_t n, int32_t dim, const float *X, const int32_t 
 
 /* Which aggregation kernel the calling thread's last gnn_aggregate_* / gnn_layer_forward / gnn_model_forward
  * call enqueued, with its template arguments and launch shape, as text in buf (HOST, cap bytes), e.g.
- * "k_aggregate<4,1,8,false,true,0> groups/block=16 ngs=32 waves/block=4 flush=ordered tiles=xcd-runs".  A
+ * "k_aggregate<4,1,8,4,false,true,0> groups/block=16 ngs=32 waves/block=4 flush=ordered tiles=xcd-runs".  A
  * benchmark uses it to tie counter readings taken with a profiler to the build that is being timed.
  * Errors: GNN_EINVAL (NULL), GNN_ELIMIT (cap too small). */
 int gnn_bench_last_aggregation(char *buf, size_t cap);

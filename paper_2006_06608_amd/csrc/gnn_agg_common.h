@@ -32,6 +32,8 @@ struct AggParams {
     int xcd_remap;
     int do_empty;    // 1: the main kernel writes the rows without entries; 0: the init kernel does
     int stream_out;  // 1: write output rows with streaming stores
+    int plain_rows;  // 1: a finished row is stored as it is (no bias, activation or scaling) with streaming stores
+    int full_rows;   // 1: one pass, every lane of a team in range: dim == chunks * dw * vector width
     int extra_blocks;  // one-block-per-tile kernel: blocks appended to the grid for the rows without entries
     int64_t tile_blocks;  // one-block-per-tile kernel: blocks that serve tiles
     int64_t nnz;

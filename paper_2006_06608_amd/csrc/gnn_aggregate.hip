@@ -98,16 +98,154 @@ __global__ __launch_bounds__(256) void k_agg_epilogue_spanning(AggParams p)
 #endif
 constexpr int kXcdRun = GNN_XCD_RUN;  // consecutive tiles that stay on one XCD
 
-// Register budget: the gather needs U*ITER*VEC registers for the rows in flight; the waves-per-SIMD
-// request keeps each variant at the occupancy its row buffer allows (8 waves: 64 registers, 7: 72,
-// 6: 80, 5: 96; the weighted and self-term variants carry a few more values) instead of landing one or two registers above a step.
-template <int VEC, int ITER, int U, bool WEIGHTED, bool SELF, int OP>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(ITER == 1 ? (WEIGHTED || SELF ? 7 : 8) : (ITER == 2 ? (WEIGHTED ? 6 : 7) : 5))))
-void k_aggregate(AggParams p)
+// The gather of one team (Sec. 4.2: the team's lanes are the dimension workers of one neighbor group):
+// for the ITER chunks that start at chunk c0, acc[c][:] = reduce over the group's staged entries of
+// w * X[col, chunk c].  U neighbour rows are in flight per lane.  GIN's own row (SELF, first group of
+// the node) is one more term of the first batch, so no load waits for another.
+template <int VEC, int ITER, int U, bool WEIGHTED, bool SELF, int OP, bool FULL>
+__device__ __forceinline__ void gather_rows(float (&acc)[ITER][VEC], const float *__restrict__ X, const int *lc,
+                                            const float *lw, int len, int node, bool self_term, float self_scale,
+                                            int dim, int dwl, int tlane, int c0)
+{
+    bool dok[ITER];
+    const float *xb = X + (size_t)(c0 * dwl + tlane) * VEC;
+#pragma unroll
+    for (int c = 0; c < ITER; ++c) {
+        dok[c] = FULL ? true : ((c0 + c) * dwl + tlane) * VEC < dim;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[c][j] = op_identity<OP>();
+    }
+    // entry -1 stands for the node's own row
+    for (int base = (SELF && self_term) ? -1 : 0; base < len; base += U) {
+        int col[U];
+        float w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            // read first, select after: positions past the group still lie inside the staged area
+            const int k = base + u;
+            const bool a = k < len;
+            const int cu = lc[k < 0 ? 0 : k];
+            col[u] = a ? cu : -1;
+            if (SELF && k < 0) col[u] = node;
+            if (WEIGHTED) {
+                const float wu = lw[k < 0 ? 0 : k];
+                w[u] = a ? wu : 0.0f;
+            }
+            if (SELF) w[u] = k < 0 ? self_scale : 1.0f;
+        }
+        float v[U][ITER][VEC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (col[u] >= 0) {
+                // 32 x 32 -> 64-bit product: one multiply-add per address
+                const float *row = xb + (size_t)(unsigned)col[u] * (unsigned)dim;
+#pragma unroll
+                for (int c = 0; c < ITER; ++c) {
+                    if (dok[c]) {
+                        load_vec<VEC>(v[u][c], row + (size_t)c * dwl * VEC);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) v[u][c][j] = op_identity<OP>();
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < ITER; ++c)
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) v[u][c][j] = op_identity<OP>();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int c = 0; c < ITER; ++c)
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    if (WEIGHTED || SELF) acc[c][j] = fmaf(w[u], v[u][c][j], acc[c][j]);
+                    else acc[c][j] = op_combine<OP>(acc[c][j], v[u][c][j]);
+                }
+    }
+}
+
+// A finished row: bias / activation / mean scaling, then the store.
+template <int VEC, int ITER>
+__device__ __forceinline__ void store_row(const AggParams &p, const float (&acc)[ITER][VEC], int node, int dwl, int tlane,
+                                          int c0)
+{
+    float *orow = p.out + (size_t)node * p.dim;
+    if (p.plain_rows) {
+        // no bias, no activation, no scaling, rows of whole cache lines: the common aggregation
+#pragma unroll
+        for (int c = 0; c < ITER; ++c) {
+            const int d = ((c0 + c) * dwl + tlane) * VEC;
+            if (d < p.dim) store_vec_stream<VEC>(orow + d, acc[c]);
+        }
+        return;
+    }
+    const float rs = row_scale(p, node);
+#pragma unroll
+    for (int c = 0; c < ITER; ++c) {
+        const int d = ((c0 + c) * dwl + tlane) * VEC;
+        if (d < p.dim) {
+            float r[VEC];
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) r[j] = epilogue(acc[c][j] * rs, p.bias, d + j, p.relu);
+            if (p.stream_out) store_vec_stream<VEC>(orow + d, r);
+            else store_vec<VEC>(orow + d, r);
+        }
+    }
+}
+
+// The kernel is wave-autonomous: a wave loads the tuples of its own teams, stages their column indices
+// in its own part of the LDS, gathers, reduces over the teams that share a target node with shuffles and
+// stores every node whose groups all sit in the wave straight from registers -- no block barrier on
+// that path, and a wave that has nothing else to do ends there.
+// Only a node whose groups straddle a wave boundary inside the block takes the block-level path of
+// Sec. 5.2: every wave that such a node continues into leaves its part of the sum in its LDS slot and
+// meets the node's leader (Algorithm 1: the node's first team in the block) at a barrier, after which
+// the leader adds the slots in wave order and flushes.  Which waves take part follows from the tuples
+// a wave holds itself: a wave whose first team does not start its node continues a node of the wave
+// before; a leader whose node reaches the end of the wave without its last group is continued behind
+// it.  Waves that do not take part have ended by then, and the barrier counts only the waves of the
+// workgroup that still run (s_barrier waits for the surviving waves of its group).
+//
+// DL >= 0 fixes the team width at compile time (dw = 2^DL lanes), which turns the per-load address
+// arithmetic into constants; DL = -1 takes it from the launch parameters.  FULL: the row is covered in one
+// pass with every lane of a team in range (dim == ITER * dw * VEC), so no lane needs a bounds check.
+// The sums over 16-byte loads of such rows get (DL, FULL = true); everything else (narrow loads, rows
+// that leave lanes idle or need several passes, max / min) runs the (DL = -1, FULL = false) form.
+template <int VEC, int ITER, int U, int DL, bool WEIGHTED, bool SELF, int OP, bool FULL>
+__global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const WsHeader *hdr = p.hdr;
     const int T = p.T;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+    const int dim = p.dim, ngs = p.ngs;
+
+    const HeaderVals hv = load_header(p.hdr);
+    if (!header_vals_ok(hv, p)) {
+        // with the ordered flush no kernel runs before this one: record why nothing was computed
+        if (p.part_rows && blockIdx.x == 0 && threadIdx.x == 0) note_stale(p.hdr, p);
+        return;
+    }
+
+    // LDS carve-up: staged indices [T*ngs + kStagePad] (and as many weights) | one slot of dim floats per
+    // wave | three flags per wave | list of rows without entries [nw][64]
+    int *s_col = reinterpret_cast<int *>(smem);
+    float *s_w = reinterpret_cast<float *>(s_col + (size_t)T * ngs + kStagePad);
+    size_t off_slot = ((size_t)T * ngs + kStagePad) * (WEIGHTED ? 2 : 1) * 4;
+    off_slot = (off_slot + 15) & ~(size_t)15;
+    float *s_slot = reinterpret_cast<float *>(smem + off_slot);   // [nw][dim]
+    int *s_last = reinterpret_cast<int *>(s_slot + (size_t)nw * dim);  // [16]: the slot's part holds the node's last group
+    int *s_more = s_last + kMaxWavesPerBlock;                     // [16]: the node continues behind this wave
+    int *s_list = s_more + kMaxWavesPerBlock;                     // [nw][64]
+
+    if ((int64_t)blockIdx.x >= p.tile_blocks) {
+        // blocks appended to the grid: rows without entries (independent of every tile)
+        const int64_t eb = (int64_t)blockIdx.x - p.tile_blocks;
+        write_empty_rows<VEC, SELF>(p, eb * nw + wave, (int64_t)p.extra_blocks * nw, s_list + wave * 64);
+        return;
+    }
     int64_t tile = blockIdx.x;
     if (p.xcd_remap) {
         // Blocks are dealt to the eight XCDs round-robin by index.  Give every XCD runs of kXcdRun
@@ -117,131 +255,85 @@ void k_aggregate(AggParams p)
         const int64_t x = blockIdx.x % kNumXcd, q = blockIdx.x / kNumXcd;
         tile = ((q / kXcdRun) * kNumXcd + x) * kXcdRun + q % kXcdRun;
     }
-    const HeaderVals hv = load_header(hdr);
-    if (!header_vals_ok(hv, p)) {
-        // with the ordered flush no kernel runs before this one: record why nothing was computed
-        if (p.part_rows && blockIdx.x == 0 && threadIdx.x == 0) note_stale(p.hdr, p);
-        return;
-    }
-
-    if ((int64_t)blockIdx.x >= p.tile_blocks) {
-        // blocks appended to the grid: rows without entries (independent of every tile)
-        const int nw = blockDim.x >> 6, wv = threadIdx.x >> 6;
-        size_t off = (size_t)(kMaxWavesPerBlock + T + (size_t)T * p.ngs * (WEIGHTED ? 2 : 1)) * 4;
-        off = ((off + 15) & ~(size_t)15) + (size_t)T * p.dim * 4;
-        int *s_list = reinterpret_cast<int *>(smem + off);
-        const int64_t eb = (int64_t)blockIdx.x - p.tile_blocks;
-        write_empty_rows<VEC, SELF>(p, eb * nw + wv, (int64_t)p.extra_blocks * nw, s_list + wv * 64);
-        return;
-    }
     const int64_t num_ng = hv.num_ng;
-    if (tile * T >= num_ng) return;  // (the grid is sized from an upper bound of the group count)
+    const int64_t g0 = tile * T;
+    if (g0 >= num_ng) return;  // (the grid is sized from an upper bound of the group count)
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int dwl_log2 = p.dwl_log2, dwl = 1 << dwl_log2;
+    const int dwl_log2 = DL >= 0 ? DL : p.dwl_log2;
+    const int dwl = 1 << dwl_log2, G = 64 >> dwl_log2;
     const int tlane = lane & (dwl - 1);
     const int team_in_wave = lane >> dwl_log2;
-    const int dim = p.dim;
+    const int team = wave * G + team_in_wave;
+    const int64_t g = g0 + team;
+    const bool valid = g < num_ng;
 
-    // LDS carve-up
-    int *s_wave_cnt = reinterpret_cast<int *>(smem);                     // [16]
-    int *s_last = s_wave_cnt + kMaxWavesPerBlock;                         // [T]
-    int *s_col = s_last + T;                                              // [T*ngs]
-    float *s_w = reinterpret_cast<float *>(s_col + (size_t)T * p.ngs);    // [T*ngs] (WEIGHTED)
-    size_t off_slot = (size_t)(kMaxWavesPerBlock + T + (size_t)T * p.ngs * (WEIGHTED ? 2 : 1)) * 4;
-    off_slot = (off_slot + 15) & ~(size_t)15;
-    float *s_slot = reinterpret_cast<float *>(smem + off_slot);           // [T*dim]
-
-    const int64_t g0 = tile * T;
-    const BlockLayout lay = block_layout(p.ng, g0, num_ng, dwl_log2, s_wave_cnt);
-    const NgEntry e = lay.e;
-
-    // stage the block's contiguous CSR range
-    const int64_t g_last = (g0 + T < num_ng ? g0 + T : num_ng) - 1;
-    const int e0 = p.ng[g0].start;
-    const int e1 = p.ng[g_last].end;
-    for (int i = tid; i < e1 - e0; i += blockDim.x) {
-        s_col[i] = load_stream(&p.colidx[e0 + i]);
-        if (WEIGHTED) s_w[i] = load_stream(&p.ew[e0 + i]);
-    }
-    for (int i = tid; i < T * dim; i += blockDim.x) s_slot[i] = op_identity<OP>();
-    for (int i = tid; i < T; i += blockDim.x) s_last[i] = 0;
-    __syncthreads();
-    const int slot = block_layout_slot(lay, dwl_log2, s_wave_cnt);
-
-    const int len = lay.valid ? e.end - e.start : 0;
-    const int off = lay.valid ? e.start - e0 : 0;
+    NgEntry e;
+    e.node = -1;
+    e.start = e.end = e.flags = 0;
+    if (valid) e = p.ng[g];
+    const int len = e.end - e.start;
     const bool first = (e.flags & 1) != 0;
 
-    // teams that continue the node of the team before them in the same wave
-    const unsigned long long cont = __ballot(lay.valid && !lay.leader && team_in_wave > 0);
-    const bool seg_head = lay.valid && (team_in_wave == 0 || lay.leader);
-    int lastflag = lay.valid ? (e.flags & 2) : 0;
+    // Stage the wave's indices: its teams' groups are consecutive, so their entries form one CSR range
+    // [ws0, ws1), which the 64 lanes copy with coalesced loads, four requests in flight per lane.
+    const int nvalid = __popcll(__ballot(valid)) >> dwl_log2;  // valid teams are a prefix of the wave
+    const int ws0 = __shfl(e.start, 0);
+    const int ws1 = __shfl(e.end, nvalid > 0 ? (nvalid << dwl_log2) - 1 : 0);
+    const int wn = nvalid > 0 ? ws1 - ws0 : 0;
+    int *wc = s_col + (size_t)wave * G * ngs;
+    float *ww = s_w + (size_t)wave * G * ngs;
+    for (int i0 = lane; i0 < wn; i0 += 256) {
+        int ci[4];
+        float wi[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i = i0 + 64 * q;
+            ci[q] = 0;
+            wi[q] = 0.0f;
+            if (i < wn) {
+                ci[q] = load_stream(&p.colidx[ws0 + i]);
+                if (WEIGHTED) wi[q] = load_stream(&p.ew[ws0 + i]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i = i0 + 64 * q;
+            if (i < wn) {
+                wc[i] = ci[q];
+                if (WEIGHTED) ww[i] = wi[q];
+            }
+        }
+    }
+    const int *lc = wc + (valid ? e.start - ws0 : 0);
+    const float *lw = ww + (valid ? e.start - ws0 : 0);
+    // (the wave reads back only what it wrote itself: program order suffices, no block barrier)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    int lastflag = valid ? (e.flags & 2) : 0;
     bool lastflag_done = false;
-    bool complete_in_wave = false;
+    bool spans_blocks = false;  // leader of a node that other tiles hold parts of
+    int block_last = 0;         // leader: a wave behind this one holds the node's last group
 
-    for (int c0 = 0; c0 < p.iter_total; c0 += ITER) {
+    for (int c0 = 0; c0 < (FULL ? 1 : p.iter_total); c0 += ITER) {
         float acc[ITER][VEC];
-        bool dok[ITER];
-        const float *xb = p.X + (size_t)(c0 * dwl + tlane) * VEC;
-#pragma unroll
-        for (int c = 0; c < ITER; ++c) {
-            dok[c] = ((c0 + c) * dwl + tlane) * VEC < dim;
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) acc[c][j] = op_identity<OP>();
-            // GIN: the node's own row enters the sum with the first group of the node, as one more
-            // term, so its load overlaps with the neighbour loads instead of following them
-            if (SELF && first && len > 0 && dok[c]) {
-                float xs[VEC];
-                load_vec<VEC>(xs, xb + (size_t)e.node * dim + (size_t)c * dwl * VEC);
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) acc[c][j] = p.self_scale * xs[j];
-            }
-        }
+        gather_rows<VEC, ITER, U, WEIGHTED, SELF, OP, FULL>(acc, p.X, lc, lw, len, e.node, first && len > 0, p.self_scale, dim, dwl,
+                                                            tlane, c0);
 
-        for (int base = 0; base < len; base += U) {
-            int col[U];
-            float w[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                // read first, select after: positions past the group still lie inside the block's LDS
-                const int k = base + u;
-                const bool a = k < len;
-                const int cu = s_col[off + k];
-                col[u] = a ? cu : -1;
-                if (WEIGHTED) {
-                    const float wu = s_w[off + k];
-                    w[u] = a ? wu : 0.0f;
-                }
-            }
-            float v[U][ITER][VEC];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-#pragma unroll
-                for (int c = 0; c < ITER; ++c) {
-                    if (col[u] >= 0 && dok[c]) {
-                        // 32 x 32 -> 64-bit product: one multiply-add per address
-                        load_vec<VEC>(v[u][c], xb + (size_t)(unsigned)col[u] * (unsigned)dim + (size_t)c * dwl * VEC);
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < VEC; ++j) v[u][c][j] = op_identity<OP>();
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int c = 0; c < ITER; ++c)
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) {
-                        if (WEIGHTED) acc[c][j] = fmaf(w[u], v[u][c][j], acc[c][j]);
-                        else acc[c][j] = op_combine<OP>(acc[c][j], v[u][c][j]);
-                    }
-        }
+        // Algorithm 1 inside the wave: a team opens a segment when its target node differs from the team's
+        // before it; the segment's first team collects the segment's sum
+        const int prev_node = __shfl_up(e.node, dwl);
+        const bool seg_head = valid && (team_in_wave == 0 || e.node != prev_node);
+        const unsigned long long cont = __ballot(valid && !seg_head);
+        const int wave_last_node = __shfl(valid ? e.node : -2, 63);  // target node of the wave's last team
+        // the wave's first team continues a node of the wave before it (inside the block)
+        const bool from_prev = seg_head && team_in_wave == 0 && wave > 0 && !first;
+        const bool leader = seg_head && !from_prev;  // Algorithm 1: first team of its (block, node) pair
 
         // segmented reduction over the teams of this wave that share a target node
         if (cont != 0ull) {
-            const int key = lay.valid ? e.node : -1;
+            const int key = valid ? e.node : -1;
             for (int o = dwl; o < 64; o <<= 1) {
                 const int okey = __shfl_down(key, o);
                 const bool take = (lane + o < 64) && key >= 0 && okey == key;
@@ -259,132 +351,127 @@ void k_aggregate(AggParams p)
             }
         }
         lastflag_done = true;
-        complete_in_wave = seg_head && first && lastflag != 0;
+        const bool complete_in_wave = seg_head && first && lastflag != 0;
+        float *orow = p.out + (size_t)(valid ? e.node : 0) * dim;
 
-        if (seg_head) {
-            if (complete_in_wave) {
-                // all groups of the node sat in this wave: store from registers
-                const float rs = row_scale(p, e.node);
-#pragma unroll
-                for (int c = 0; c < ITER; ++c) {
-                    const int d = ((c0 + c) * dwl + tlane) * VEC;
-                    if (d < dim) {
-                        float r[VEC];
-#pragma unroll
-                        for (int j = 0; j < VEC; ++j) r[j] = epilogue(acc[c][j] * rs, p.bias, d + j, p.relu);
-                        if (p.stream_out) store_vec_stream<VEC>(p.out + (size_t)e.node * dim + d, r);
-                        else store_vec<VEC>(p.out + (size_t)e.node * dim + d, r);
-                    }
-                }
-            } else if (!p.part_rows) {
-                // the node continues in another wave (or block): accumulate in its LDS slot
-                float *srow = s_slot + (size_t)slot * dim;
+        // all groups of the node sat in this wave: store from registers
+        if (complete_in_wave) store_row<VEC, ITER>(p, acc, e.node, dwl, tlane, c0);
+
+        // Block-level path (Sec. 5.2).  `reaches` : the team's node extends to the end of the wave;
+        // `goes_on`: ... and its last group lies behind this wave, in this block.
+        const bool reaches = valid && wave_last_node == e.node;
+        const bool goes_on = reaches && lastflag == 0 && wave + 1 < nw && g0 + (int64_t)(wave + 1) * G < num_ng;
+        const bool waits = leader && !complete_in_wave && goes_on;  // a leader that others hand their parts to
+        if (__any(from_prev || waits)) {
+            if (from_prev) {
+                float *srow = s_slot + (size_t)wave * dim;
 #pragma unroll
                 for (int c = 0; c < ITER; ++c) {
                     const int d = ((c0 + c) * dwl + tlane) * VEC;
                     if (d < dim) {
 #pragma unroll
-                        for (int j = 0; j < VEC; ++j) atomicAdd(&srow[d + j], acc[c][j]);
+                        for (int j = 0; j < VEC; ++j) srow[d + j] = acc[c][j];
                     }
                 }
-                if (lastflag != 0 && tlane == 0) s_last[slot] = 1;
+                if (tlane == 0) {
+                    s_last[wave] = lastflag;
+                    s_more[wave] = goes_on ? 1 : 0;
+                }
             }
-        }
-        if (p.part_rows) {
-            // ordered flush: the waves add to the slots one after the other, in wave order (the
-            // segment heads of one wave have distinct target nodes, so plain read-modify-writes do)
-            const bool add = seg_head && !complete_in_wave;
-            const int nw = blockDim.x >> 6;
-            for (int w = 0; w < nw; ++w) {
-                if ((tid >> 6) == w && add) {
-                    float *srow = s_slot + (size_t)slot * dim;
+            __syncthreads();  // producers and waiting leaders only: every other wave of the block has ended or will
+            if (waits) {
+                for (int w2 = wave + 1; w2 < nw; ++w2) {
+                    const float *srow = s_slot + (size_t)w2 * dim;
 #pragma unroll
                     for (int c = 0; c < ITER; ++c) {
                         const int d = ((c0 + c) * dwl + tlane) * VEC;
                         if (d < dim) {
 #pragma unroll
-                            for (int j = 0; j < VEC; ++j) srow[d + j] = op_combine<OP>(srow[d + j], acc[c][j]);
+                            for (int j = 0; j < VEC; ++j) acc[c][j] = op_combine<OP>(acc[c][j], srow[d + j]);
                         }
                     }
-                    if (lastflag != 0 && tlane == 0) s_last[slot] = 1;
+                    block_last |= s_last[w2];
+                    if (s_more[w2] == 0) break;
                 }
-                __syncthreads();
+            }
+            if (!FULL && c0 + ITER < p.iter_total) __syncthreads();  // the slots are written again in the next pass
+        }
+
+        // leader flush (Algorithm 1) of a node that the wave alone did not finish
+        if (leader && !complete_in_wave) {
+            const bool complete = first && (lastflag | block_last) != 0;  // the block holds all groups of the node
+            spans_blocks = !complete;
+            // ordered flush: the node of the block's first group goes to partial row 0 of the tile, any other
+            // unfinished node (it can only be the node of the last group) to partial row 1
+            float *prow = p.part_rows ? p.part_rows + ((size_t)tile * 2 + (team == 0 ? 0 : 1)) * dim : nullptr;
+#pragma unroll
+            for (int c = 0; c < ITER; ++c) {
+                const int d = ((c0 + c) * dwl + tlane) * VEC;
+                if (d < dim) {
+                    float r[VEC];
+                    if (complete) {
+                        const float rs = row_scale(p, e.node);
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) r[j] = epilogue(acc[c][j] * rs, p.bias, d + j, p.relu);
+                        if (p.stream_out) store_vec_stream<VEC>(orow + d, r);
+                        else store_vec<VEC>(orow + d, r);
+                    } else if (prow) {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) r[j] = acc[c][j];
+                        store_vec_coherent<VEC>(prow + d, r);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) atomicAdd(&orow[d + j], acc[c][j]);
+                    }
+                }
             }
         }
     }
-    __syncthreads();
 
-    // leader flush (Algorithm 1): one team per slot moves the block's partial row to global memory
-    if (lay.leader && !complete_in_wave) {
-        const bool complete = first && s_last[slot] != 0;
-        const float *srow = s_slot + (size_t)slot * dim;
+    if (spans_blocks && p.part_rows) {
+        // The node spans the tiles b0..b1.  Every one of them publishes its partial row (the
+        // stores above have completed once the wait below returns), then counts itself in; the
+        // block that arrives last adds the partial rows in tile order, applies bias/activation
+        // and writes the row, so the result does not depend on timing.
+        // (a workgroup-scope fence alone does not wait for the write-through stores: the explicit
+        // wait keeps the counter from overtaking them on its way to another memory channel)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         float *orow = p.out + (size_t)e.node * dim;
-        // ordered flush: the node of the block's first group goes to partial row 0 of the tile, any
-        // other unfinished node (it can only be the node of the last group) to partial row 1
-        float *prow = p.part_rows ? p.part_rows + ((size_t)tile * 2 + (lay.team == 0 ? 0 : 1)) * dim : nullptr;
-        for (int c = 0; c < p.iter_total; ++c) {
-            const int d = (c * dwl + tlane) * VEC;
-            if (d >= dim) break;
-            float r[VEC];
+        int arrived = 0;
+        if (tlane == 0) arrived = atomicAdd(&p.cnt[e.node], 1);
+        arrived = __shfl(arrived, lane - tlane);
+        const int gfirst = p.ngptr[e.node], gend = p.ngptr[e.node + 1];
+        const int64_t b0 = gfirst / T, b1 = (gend - 1) / T;
+        if (arrived == (int)(b1 - b0)) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            if (tlane == 0) p.cnt[e.node] = 0;  // ready for the next call
+            // in its first tile the node is the tile's first node only if it starts the tile
+            const float *first_row = p.part_rows + ((size_t)b0 * 2 + (gfirst % T == 0 ? 0 : 1)) * dim;
+            for (int c = 0; c < p.iter_total; ++c) {
+                const int d = (c * dwl + tlane) * VEC;
+                if (d >= dim) break;
+                float sum[VEC];
+                load_vec_coherent<VEC>(sum, first_row + d);
+                for (int64_t b = b0 + 1; b <= b1; b += 4) {
+                    float t[4][VEC];
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) r[j] = srow[d + j];
-            if (complete) {
+                    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) t[q][j] = op_identity<OP>();
+                        if (b + q <= b1) load_vec_coherent<VEC>(t[q], p.part_rows + ((size_t)(b + q) * 2) * dim + d);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (b + q <= b1) {
+#pragma unroll
+                            for (int j = 0; j < VEC; ++j) sum[j] = op_combine<OP>(sum[j], t[q][j]);
+                        }
+                }
                 const float rs = row_scale(p, e.node);
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) r[j] = epilogue(r[j] * rs, p.bias, d + j, p.relu);
-                if (p.stream_out) store_vec_stream<VEC>(orow + d, r);
-                else store_vec<VEC>(orow + d, r);
-            } else if (prow) {
-                store_vec_coherent<VEC>(prow + d, r);
-            } else {
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) atomicAdd(&orow[d + j], r[j]);
-            }
-        }
-        if (!complete && prow) {
-            // The node spans the tiles b0..b1.  Every one of them publishes its partial row (the
-            // stores above have completed once the wait below returns), then counts itself in; the
-            // block that arrives last adds the partial rows in tile order, applies bias/activation
-            // and writes the row, so the result does not depend on timing.
-            // (a workgroup-scope fence alone does not wait for the write-through stores: the explicit
-            // wait keeps the counter from overtaking them on its way to another memory channel)
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            int arrived = 0;
-            if (tlane == 0) arrived = atomicAdd(&p.cnt[e.node], 1);
-            arrived = __shfl(arrived, lane - tlane);
-            const int gfirst = p.ngptr[e.node], gend = p.ngptr[e.node + 1];
-            const int64_t b0 = gfirst / T, b1 = (gend - 1) / T;
-            if (arrived == (int)(b1 - b0)) {
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                if (tlane == 0) p.cnt[e.node] = 0;  // ready for the next call
-                // in its first tile the node is the tile's first node only if it starts the tile
-                const float *first_row = p.part_rows + ((size_t)b0 * 2 + (gfirst % T == 0 ? 0 : 1)) * dim;
-                for (int c = 0; c < p.iter_total; ++c) {
-                    const int d = (c * dwl + tlane) * VEC;
-                    if (d >= dim) break;
-                    float sum[VEC];
-                    load_vec_coherent<VEC>(sum, first_row + d);
-                    for (int64_t b = b0 + 1; b <= b1; b += 4) {
-                        float t[4][VEC];
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                            for (int j = 0; j < VEC; ++j) t[q][j] = op_identity<OP>();
-                            if (b + q <= b1) load_vec_coherent<VEC>(t[q], p.part_rows + ((size_t)(b + q) * 2) * dim + d);
-                        }
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            if (b + q <= b1) {
-#pragma unroll
-                                for (int j = 0; j < VEC; ++j) sum[j] = op_combine<OP>(sum[j], t[q][j]);
-                            }
-                    }
-                    const float rs = row_scale(p, e.node);
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) sum[j] = epilogue(sum[j] * rs, p.bias, d + j, p.relu);
-                    store_vec<VEC>(orow + d, sum);
-                }
+                for (int j = 0; j < VEC; ++j) sum[j] = epilogue(sum[j] * rs, p.bias, d + j, p.relu);
+                store_vec<VEC>(orow + d, sum);
             }
         }
     }
@@ -445,28 +532,52 @@ void launch_agg_epilogue_spanning(const AggParams &p, hipStream_t s)
     hipLaunchKernelGGL(k_agg_epilogue_spanning, dim3((unsigned)blocks), dim3(256), 0, s, p);
 }
 
+template <int VEC, int ITER, int U, int DL, bool FULL>
+static void launch_one(int op, bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s,
+                       const AggParams &p)
+{
+    if (op == kOpMax) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, -1, false, false, kOpMax, false>), grid, block, lds, s, p);
+    else if (op == kOpMin) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, -1, false, false, kOpMin, false>), grid, block, lds, s, p);
+    else if (self) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, DL, false, true, kOpSum, FULL>), grid, block, lds, s, p);
+    else if (weighted) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, DL, true, false, kOpSum, FULL>), grid, block, lds, s, p);
+    else hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, DL, false, false, kOpSum, FULL>), grid, block, lds, s, p);
+}
+
+// The sums over 16-byte loads whose rows are covered in one pass with no idle lane (dim = chunks x team
+// width x 4: 16, 32, 64, 96, 128, ... with the model's team width) get the team width as a compile-time
+// constant and no bounds checks; everything else takes the generic form.
 template <int VEC, int ITER, int U>
 static void launch_main(int op, bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s,
                         const AggParams &p)
 {
-    if (op == kOpMax) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, false, kOpMax>), grid, block, lds, s, p);
-    else if (op == kOpMin) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, false, kOpMin>), grid, block, lds, s, p);
-    else if (self) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, true, kOpSum>), grid, block, lds, s, p);
-    else if (weighted) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, true, false, kOpSum>), grid, block, lds, s, p);
-    else hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, false, false, kOpSum>), grid, block, lds, s, p);
+    if constexpr (VEC == 4) {
+        if (p.full_rows && op == kOpSum) {
+            switch (p.dwl_log2) {
+                case 0: launch_one<VEC, ITER, U, 0, true>(op, weighted, self, grid, block, lds, s, p); break;
+                case 1: launch_one<VEC, ITER, U, 1, true>(op, weighted, self, grid, block, lds, s, p); break;
+                case 2: launch_one<VEC, ITER, U, 2, true>(op, weighted, self, grid, block, lds, s, p); break;
+                case 3: launch_one<VEC, ITER, U, 3, true>(op, weighted, self, grid, block, lds, s, p); break;
+                case 4: launch_one<VEC, ITER, U, 4, true>(op, weighted, self, grid, block, lds, s, p); break;
+                case 5: launch_one<VEC, ITER, U, 5, true>(op, weighted, self, grid, block, lds, s, p); break;
+                default: launch_one<VEC, ITER, U, 6, true>(op, weighted, self, grid, block, lds, s, p); break;
+            }
+            return;
+        }
+    }
+    launch_one<VEC, ITER, U, -1, false>(op, weighted, self, grid, block, lds, s, p);
 }
 
 // ---- what the calling thread launched last (gnn_bench_last_aggregation) ----
 struct LastLaunch {
     const char *kernel;
-    int vec, iter, u, weighted, self, op, T, ngs, wpb, ordered, xcd;
+    int vec, iter, u, dl, weighted, self, op, T, ngs, wpb, ordered, xcd;
 };
-static thread_local LastLaunch g_last = {"none", 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+static thread_local LastLaunch g_last = {"none", 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-void note_launch(const char *kernel, int vec, int iter, int u, bool weighted, bool self, int op, int T, int ngs, int wpb,
-                 bool ordered, bool xcd)
+void note_launch(const char *kernel, int vec, int iter, int u, int dl, bool weighted, bool self, int op, int T, int ngs,
+                 int wpb, bool ordered, bool xcd)
 {
-    g_last = LastLaunch{kernel, vec, iter, u, weighted ? 1 : 0, self ? 1 : 0, op, T, ngs, wpb, ordered ? 1 : 0, xcd ? 1 : 0};
+    g_last = LastLaunch{kernel, vec, iter, u, dl, weighted ? 1 : 0, self ? 1 : 0, op, T, ngs, wpb, ordered ? 1 : 0, xcd ? 1 : 0};
 }
 
 // U of launch_vec below, for the launch description
@@ -568,6 +679,8 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     p.extra_blocks = 0;
     const int units = (dim + vec - 1) / vec;
     p.iter_total = (units + dw - 1) / dw;
+    p.plain_rows = (p.stream_out && !bias && !relu && !mean) ? 1 : 0;
+    p.full_rows = (p.iter_total <= 4 && p.iter_total * dw * vec == dim) ? 1 : 0;
 
     const int64_t ng_cap = L.ng_capacity;
     const bool weighted = ew != nullptr;
@@ -582,7 +695,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
             else hipLaunchKernelGGL(k_aggregate_noblock<false>, dim3((unsigned)blocks), dim3(256), 0, s, p);
         }
         if (bias || relu) hipLaunchKernelGGL(k_epilogue_all, dim3(2048), dim3(256), 0, s, p);
-        note_launch("k_aggregate_noblock", 1, 1, 1, weighted, self, op, 1, ngs, 4, false, false);
+        note_launch("k_aggregate_noblock", 1, 1, 1, -1, weighted, self, op, 1, ngs, 4, false, false);
         GNN_HIP_TRY(hipGetLastError());
         return GNN_OK;
     }
@@ -614,7 +727,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
             if (rc < 0) return rc;
             if (rc == GNN_OK) {
                 const int it_f = p.iter_total < 4 ? p.iter_total : 4;
-                note_launch("k_gin_layer_fused", vec, it_f, unroll_of(vec, it_f), false, true, op, pf.T, ngs, wpb_f, true,
+                note_launch("k_gin_layer_fused", vec, it_f, unroll_of(vec, it_f), -1, false, true, op, pf.T, ngs, wpb_f, true,
                             p.xcd_remap != 0);
                 if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
                 fuse->done = true;
@@ -668,7 +781,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
             if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
             const int rc = launch_aggregate_pipe(vec, iter, weighted, self, blocks, wpb, plds, s, p);
             if (rc != GNN_OK) return rc;
-            note_launch("k_aggregate_pipe", vec, iter, unroll_of(vec, iter), weighted, self, op, T, ngs, wpb, false,
+            note_launch("k_aggregate_pipe", vec, iter, unroll_of(vec, iter), -1, weighted, self, op, T, ngs, wpb, false,
                         p.xcd_remap != 0);
             if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
             if (bias || relu)
@@ -701,7 +814,8 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
         else if (vec == 2) launch_vec<2>(op, iter, weighted, self, g, b, lds, s, p);
         else launch_vec<1>(op, iter, weighted, self, g, b, lds, s, p);
     }
-    note_launch("k_aggregate", vec, iter, unroll_of(vec, iter), weighted && op == kOpSum, self && op == kOpSum, op, T, ngs,
+    note_launch("k_aggregate", vec, iter, unroll_of(vec, iter), (vec == 4 && op == kOpSum && p.full_rows) ? dwl_log2 : -1,
+                weighted && op == kOpSum, self && op == kOpSum, op, T, ngs,
                 wpb, ordered, p.xcd_remap != 0);
     if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
     if (!ordered && (bias || relu))
@@ -746,9 +860,9 @@ int gnn_bench_last_aggregation(char *buf, size_t cap)
 {
     if (!buf || cap == 0) return GNN_EINVAL;
     const LastLaunch &l = g_last;
-    const int k = snprintf(buf, cap, "%s<%d,%d,%d,%s,%s,%d> groups/block=%d ngs=%d waves/block=%d flush=%s tiles=%s",
-                           l.kernel, l.vec, l.iter, l.u, l.weighted ? "true" : "false", l.self ? "true" : "false", l.op,
-                           l.T, l.ngs, l.wpb, l.ordered ? "ordered" : "atomic", l.xcd ? "xcd-runs" : "round-robin");
+    const int k = snprintf(buf, cap, "%s<%d,%d,%d,%d,%s,%s,%d> groups/block=%d ngs=%d waves/block=%d flush=%s tiles=%s",
+                           l.kernel, l.vec, l.iter, l.u, l.dl, l.weighted ? "true" : "false", l.self ? "true" : "false",
+                           l.op, l.T, l.ngs, l.wpb, l.ordered ? "ordered" : "atomic", l.xcd ? "xcd-runs" : "round-robin");
     return (k < 0 || (size_t)k >= cap) ? GNN_ELIMIT : GNN_OK;
 }
 

@@ -97,15 +97,19 @@ inline size_t part_rows_bytes(int64_t ng_capacity, int tile, int32_t dim)
     return align_up(sizeof(float) * 2 * (size_t)(tiles > 0 ? tiles : 1) * (size_t)dim);
 }
 
-// LDS bytes of one block of the one-block-per-tile aggregation kernel: per-wave leader counts, one
-// "saw the node's last group" flag per group, the staged column indices (and weights) of the block's
-// T groups of up to ngs entries, one slot of dim floats per group (Algorithm 1), and a 64-entry list of
-// rows without entries per wave.  T = waves_per_block * 64 / dw.
+// LDS bytes of one block of the one-block-per-tile aggregation kernel: the staged column indices (and
+// weights) of the block's T groups of up to ngs entries plus kStagePad entries that a batch of reads may
+// run over, one slot of dim floats per wave (the part of a node's sum that a wave hands to the node's
+// leader, Sec. 5.2), two flags per wave, and a 64-entry list of rows without entries per wave.
+// T = waves_per_block * 64 / dw.
+constexpr int kStagePad = 8;
+
 inline size_t agg_lds_bytes(int T, int32_t ngs, int32_t dim, int wpb, bool weighted)
 {
-    size_t b = (size_t)(kMaxWavesPerBlock + T + (size_t)T * ngs * (weighted ? 2 : 1)) * 4;
+    size_t b = ((size_t)T * ngs + kStagePad) * (weighted ? 2 : 1) * 4;
     b = (b + 15) & ~(size_t)15;
-    b += (size_t)T * dim * 4;
+    b += (size_t)wpb * dim * 4;
+    b += (size_t)2 * kMaxWavesPerBlock * 4;
     b += (size_t)wpb * 64 * 4;
     return b;
 }

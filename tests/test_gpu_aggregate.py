@@ -363,7 +363,7 @@ def test_random_graphs_and_parameter_combinations(seed):
         # blocks of fewer than 16 groups, for whose partial rows gnn_workspace_bytes leaves no room
         r_ngs, r_dw, r_wpb = gnn.gnn_decide(n, nnz, 0, dim, ngs, dw, wpb)
         T = r_wpb * (64 // r_dw)
-        lds = -(-4 * (16 + T + T * r_ngs * (2 if weighted else 1)) // 16) * 16 + 4 * T * dim + 256 * r_wpb
+        lds = -(-4 * (T * r_ngs + 8) * (2 if weighted else 1) // 16) * 16 + 4 * r_wpb * dim + 128 + 256 * r_wpb
         if e.code == -5:
             assert lds > 65536, f"GNN_ELIMIT although a block needs only {lds} bytes: {what}"
         else:
@@ -372,7 +372,7 @@ def test_random_graphs_and_parameter_combinations(seed):
     r_ngs, r_dw, r_wpb = gnn.gnn_decide(n, nnz, 0, dim, ngs, dw, wpb)
     T = r_wpb * (64 // r_dw)
     if not flags & (gnn.GNN_FLAG_NO_BLOCK_OPT | gnn.GNN_FLAG_DETERMINISTIC):
-        lds = -(-4 * (16 + T + T * r_ngs * (2 if weighted else 1)) // 16) * 16 + 4 * T * dim + 256 * r_wpb
+        lds = -(-4 * (T * r_ngs + 8) * (2 if weighted else 1) // 16) * 16 + 4 * r_wpb * dim + 128 + 256 * r_wpb
         assert lds <= 65536, f"accepted although a block needs {lds} bytes: {what}"
     assert_parity(got, ref, ab, what)
 

@@ -186,7 +186,8 @@ def test_every_node_spans_many_blocks_and_integer_sums_are_exact(dim, dw):
     G, Gw = DeviceGraph(rp, ci), DeviceGraph(rp, ci, ew)
     ref_gin = oracle.aggregate_gin(rp, ci, 1.0, X)       # (1 + eps) = 2: still integers
     ref_gcn = oracle.aggregate_gcn(rp, ci, ew, X)
-    ws = gnn.alloc_workspace(n, ci.size, dim, 1)
+    # (the workspace allows partial rows for blocks of at least 16 groups: blocks of 4 need four times the room)
+    ws = gnn.alloc_workspace(n, ci.size, 4 * dim, 1)
     for rep in range(20):
         got = run_gin(G, 1.0, X, ngs=1, dw=dw, wpb=1, flags=DET, ws=ws)
         assert np.array_equal(got.view(np.uint32), ref_gin.view(np.uint32)), f"GIN, repetition {rep}"
@@ -197,7 +198,7 @@ def test_every_node_spans_many_blocks_and_integer_sums_are_exact(dim, dw):
     Xs = rng.integers(-3, 4, size=(6001, dim)).astype(np.float32)
     Gs = DeviceGraph(star_rp, star_ci)
     ref = oracle.aggregate_gin(star_rp, star_ci, 0.0, Xs)
-    wss = gnn.alloc_workspace(6001, star_ci.size, dim, 1)
+    wss = gnn.alloc_workspace(6001, star_ci.size, 4 * dim, 1)
     for rep in range(5):
         got = run_gin(Gs, 0.0, Xs, ngs=1, dw=dw, wpb=1, flags=DET, ws=wss)
         assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), f"hubs, repetition {rep}"

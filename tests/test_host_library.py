@@ -152,7 +152,7 @@ def test_the_models_own_choice_always_fits_the_scratch_memory_of_a_block():
 
     def need(dim, ngs, dw, wpb):
         T = wpb * (64 // dw)
-        return -(-4 * (16 + T + 2 * T * ngs) // 16) * 16 + 4 * T * dim + 256 * wpb
+        return -(-4 * 2 * (T * ngs + 8) // 16) * 16 + 4 * wpb * dim + 128 + 256 * wpb
 
     dims = list(range(1, 70)) + [96, 100, 128, 200, 256, 500, 512, 1000, 1024, 1433, 2048, 3703, 4096, 8192, 12000, 15000]
     for dim in dims:
