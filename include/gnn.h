@@ -67,11 +67,8 @@ extern "C" {
                                        follow communities, 1-3 % less run time.  The library uses this
                                        order by itself from ngs = 16 on; the flag asks for it with smaller
                                        groups too (measured slower there) */
-#define GNN_FLAG_NO_PIPELINE 8u     /* always one block per tile (the general kernel) */
-#define GNN_FLAG_PIPELINE 16u       /* persistent, software-pipelined blocks whenever their requirements
-                                       hold (a block serves <= 64 groups, a wave <= 512 index entries);
-                                       without either flag the library pipelines when ngs <= 8, where the
-                                       per-tile latency chain dominates */
+#define GNN_FLAG_NO_PIPELINE 8u     /* accepted and ignored (kept for callers of an earlier version, which had */
+#define GNN_FLAG_PIPELINE 16u       /* a second, persistent kernel that these two flags forbade / forced)      */
 #define GNN_FLAG_DETERMINISTIC 32u  /* require the ordered flush (bitwise identical results from run to run
                                        for fixed ngs, dw, waves): no float atomics.  The waves of a block add
                                        to a shared slot in wave order; a block leaves the partial rows of nodes
@@ -88,9 +85,10 @@ extern "C" {
                                        the aggregation kernel where the shape allows (in_dim <= 128 and a
                                        multiple of 4, out_dim <= 64, <= 8 waves per block, a multiple of
                                        ceil(out_dim/16), workspace with room for the ordered flush).  The
-                                       library fuses by itself when the mean row has fewer than 8 entries
-                                       (batches of small graphs: one launch per layer, -20 %); on graphs with
-                                       long rows the two separate kernels are faster, hence the flag */
+                                       library fuses by itself when the mean row has fewer than 8 entries and
+                                       the layer's input is at most 160 MB (batches of small graphs: one launch
+                                       per layer, -20 %); on graphs with long rows and on inputs beyond the
+                                       memory-side cache the two separate kernels are faster, hence the flag */
 #define GNN_FLAG_NO_FUSION 512u     /* never fuse */
 #define GNN_FLAG_ATOMIC_FLUSH 128u  /* always finish nodes that span blocks the way Sec. 5.2 describes: the
                                        leader adds the block's partial row to global memory with one float
@@ -235,7 +233,7 @@ int gnn_aggregate_gin_static(int32_t n, int64_t nnz, const int32_t *rowptr, cons
  * self term.  op: GNN_REDUCE_SUM, GNN_REDUCE_MAX, GNN_REDUCE_MIN (elementwise, exact) or
  * GNN_REDUCE_MEAN (sum divided by the row length).  A row without entries gives 0.  Max, min and mean
  * use the ordered flush, so the workspace must be sized with max_dim >= dim (GNN_EWORKSPACE otherwise)
- * and the flags GNN_FLAG_NO_BLOCK_OPT, _ATOMIC_FLUSH, _PIPELINE, _FUSION are refused (GNN_EINVAL).
+ * and the flags GNN_FLAG_NO_BLOCK_OPT, _ATOMIC_FLUSH, _FUSION are refused (GNN_EINVAL).
  * Everything else as for gnn_aggregate_gcn. */
 #define GNN_REDUCE_SUM 0
 #define GNN_REDUCE_MAX 1

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libgnn_mi355x.so")
-SOURCES = ["gnn_host.cpp", "gnn_partition.hip", "gnn_aggregate.hip", "gnn_aggregate_pipe.hip", "gnn_gin_fused.hip", "gnn_update.hip", "gnn_backward.hip", "gnn_reorder_device.hip", "gnn_microbench.hip"]
+SOURCES = ["gnn_host.cpp", "gnn_partition.hip", "gnn_aggregate.hip", "gnn_gin_fused.hip", "gnn_update.hip", "gnn_backward.hip", "gnn_reorder_device.hip", "gnn_microbench.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]

@@ -217,27 +217,23 @@ void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, in
     const double avg = n > 0 ? (double)nnz / (double)n : 0.0;
     const bool auto_dw = *dw <= 0;
     // dimension workers: lanes per neighbor row.  Each lane moves `vec` floats per load and owns up
-    // to 4 chunks of the row.  A lane should have about 8 independent loads in flight; a row of at
-    // most 4 neighbors supplies them in one batch only if the lane takes two chunks (a two-chunk lane
-    // batches 4 neighbors; measured on batches of small graphs: 25 % faster at Dim 64, while rows of
-    // 5..8 neighbors would need a second batch and gain nothing).  Among the
-    // admissible powers of two take the one that leaves the fewest lane slots idle
-    // (dw * chunks - row length in vectors), and among equals the widest team (fewest chunks).
+    // to 4 chunks of the row.  Measured on MI355X (sweeps over dw at Dim 16 ... 256 on five kinds of
+    // graphs): the best team is the one whose single load instruction covers exactly one 128-byte cache
+    // line of the row -- 8 lanes of 16 bytes -- so that a wavefront requests 8 distinct lines per
+    // instruction and a lane keeps several chunks x neighbours in flight; wider teams (one chunk per lane)
+    // were 5-11 % slower at Dim 128-256 and narrower ones (half a line per load) 6-14 % slower.  Rows
+    // shorter than a line get the power of two that covers them; rows longer than 3 lines widen the team
+    // until 3 chunks suffice.  A row of at most 4 neighbors fills a lane's loads in flight only if the
+    // lane takes two chunks (measured on batches of small graphs: 25 % faster at Dim 64), so a one-chunk
+    // team is halved there.
     if (auto_dw) {
         const int units = (dim + vec - 1) / vec;
-        const bool short_rows = avg <= 4.0;
-        const int min_chunks = (short_rows && units >= 2) ? 2 : 1;
-        int best = 64, best_waste = 1 << 30;
-        for (int d = 1; d <= 64; d *= 2) {
-            const int chunks = (units + d - 1) / d;
-            if (chunks > 4 || chunks < min_chunks) continue;
-            const int waste = d * chunks - units;
-            if (waste <= best_waste) {
-                best_waste = waste;
-                best = d;
-            }
-        }
-        *dw = best;
+        const int line_lanes = 128 / (4 * vec);
+        int d = 1;
+        while (d < units && d < line_lanes) d *= 2;
+        while (d < 64 && (units + d - 1) / d > 3) d *= 2;  // (four chunks leave only two neighbours in flight: 7 % slower at Dim 128)
+        if (avg <= 4.0 && d > 1 && (units + d - 1) / d == 1 && units >= 2) d /= 2;
+        *dw = d;
     }
     // neighbor-group size, from the graph alone so that one partition serves every layer of a
     // model.  Time ~ (#groups * per-group cost) + (#entries * per-row cost): bigger groups mean
@@ -248,6 +244,8 @@ void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, in
     if (*ngs <= 0) {
         int g = 16;
         while (g < 32 && (double)g < 2.0 * avg) g *= 2;
+        // long rows (a dense graph, mean row 500: 128 is 8 % faster than 32): fewer parts to combine
+        while (g < 128 && (double)g * 4.0 <= avg) g *= 2;
         if (max_degree > 0)
             while (g > 16 && g / 2 >= max_degree) g /= 2;
         *ngs = g;

@@ -38,14 +38,6 @@ inline int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, c
 void launch_agg_init(const AggParams &p, bool self, hipStream_t s);
 void launch_agg_epilogue_spanning(const AggParams &p, hipStream_t s);
 
-// gnn_aggregate_pipe.hip: the persistent, software-pipelined kernel.  pipe_lds_bytes returns 0 when
-// the shape does not qualify; pipe_blocks returns the number of resident blocks to launch (0: do not
-// use the kernel, < 0: error).
-size_t pipe_lds_bytes(int T, int dim, int ngs, int dwl_log2, int wpb, bool weighted);
-int pipe_blocks(int vec, int iter, bool weighted, bool self, int cus, int wpb, size_t lds, int64_t tiles_upper, int n);
-int launch_aggregate_pipe(int vec, int iter, bool weighted, bool self, int blocks, int wpb, size_t lds, hipStream_t s,
-                          AggParams &p);
-
 // gnn_gin_fused.hip: GIN aggregation with the Update fused in, on the general kernel with the ordered
 // flush; p.part_rows must have room for rows of max(p.dim, M) floats.  Returns GNN_OK when the fused
 // kernel was launched, 1 when the shape does not qualify (nothing launched), < 0 on error.

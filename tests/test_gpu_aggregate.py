@@ -102,25 +102,25 @@ def test_result_does_not_depend_on_block_size_or_xcd_order(wpb, kind):
     ref, ab = oracle.aggregate_gin(rp, ci, 0.0, X, want_abs=True)
     G = DeviceGraph(rp, ci)
     for ngs in (4, 32):
-        for flags in (0, gnn.GNN_FLAG_XCD_RUNS, gnn.GNN_FLAG_PIPELINE, gnn.GNN_FLAG_NO_PIPELINE,
-                      gnn.GNN_FLAG_PIPELINE | gnn.GNN_FLAG_XCD_RUNS):
+        for flags in (0, gnn.GNN_FLAG_XCD_RUNS, gnn.GNN_FLAG_ATOMIC_FLUSH, gnn.GNN_FLAG_PIPELINE,
+                      gnn.GNN_FLAG_ATOMIC_FLUSH | gnn.GNN_FLAG_XCD_RUNS):
             assert_parity(run_gin(G, 0.0, X, ngs=ngs, dw=16, wpb=wpb, flags=flags), ref, ab,
                           f"wpb {wpb} ngs {ngs} flags {flags}")
 
 
 @pytest.mark.parametrize("kind", ["powerlaw", "rmat", "star"])
 @pytest.mark.parametrize("dim,ngs", [(16, 8), (64, 32), (96, 16), (22, 4), (3, 2), (130, 8)])
-def test_both_kernels_agree_with_the_oracle(kind, dim, ngs):
+def test_both_flushes_agree_with_the_oracle(kind, dim, ngs):
     rp, ci = _graph(kind)
     ew = oracle.gcn_norm(rp, ci)
     X = features(rp.size - 1, dim, seed=300 + dim)
     ref, ab = oracle.aggregate_gcn(rp, ci, ew, X, want_abs=True)
     G = DeviceGraph(rp, ci, ew)
-    for flags in (gnn.GNN_FLAG_PIPELINE, gnn.GNN_FLAG_NO_PIPELINE):
+    for flags in (0, gnn.GNN_FLAG_ATOMIC_FLUSH):
         assert_parity(run_gcn(G, X, ngs=ngs, flags=flags), ref, ab, f"gcn {kind} dim {dim} flags {flags}")
     ref, ab = oracle.aggregate_gin(rp, ci, 0.5, X, want_abs=True)
     G2 = DeviceGraph(rp, ci)
-    for flags in (gnn.GNN_FLAG_PIPELINE, gnn.GNN_FLAG_NO_PIPELINE):
+    for flags in (0, gnn.GNN_FLAG_ATOMIC_FLUSH):
         assert_parity(run_gin(G2, 0.5, X, ngs=ngs, flags=flags), ref, ab, f"gin {kind} dim {dim} flags {flags}")
 
 

@@ -301,6 +301,8 @@ def test_fusion_is_automatic_for_short_rows_and_can_be_switched_off():
         gnn.gnn_workspace_status(ws)
         outs.append(out.cpu().numpy())
         assert_parity(outs[-1], ref, scale, f"gin layer flags {flags}")
+        fused = gnn.gnn_bench_last_aggregation().startswith("k_gin_layer_fused")
+        assert fused == (flags != gnn.GNN_FLAG_NO_FUSION), (flags, gnn.gnn_bench_last_aggregation())
     assert np.array_equal(outs[0].view(np.uint32), outs[2].view(np.uint32))  # automatic == requested fusion
     assert np.array_equal(outs[0].view(np.uint32), outs[3].view(np.uint32))  # the fused kernel is deterministic
 

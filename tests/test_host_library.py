@@ -140,7 +140,7 @@ def test_paper_model_literal_and_decide_ranges():
     for n, nnz, dim in [(2708, 13264, 16), (19717, 108365, 3), (44246, 165028, 64), (410236, 5289110, 96),
                         (1 << 20, 16085932, 64), (1000, 5000, 22), (1000, 5000, 1323)]:
         ngs, dw, wpb = gnn.gnn_decide(n, nnz, 0, dim)
-        assert 1 <= ngs <= 64 and 1 <= wpb <= 16
+        assert 1 <= ngs <= 128 and 1 <= wpb <= 16
         assert 1 <= dw <= 64 and dw & (dw - 1) == 0
 
 
@@ -160,7 +160,7 @@ def test_the_models_own_choice_always_fits_the_scratch_memory_of_a_block():
             n = int(rng.integers(1, 2_000_000))
             nnz = int(n * rng.choice([0.0, 0.5, 3.7, 15.0, 60.0, 500.0]))
             ngs, dw, wpb = gnn.gnn_decide(n, nnz, int(rng.choice([0, 3, 40, 100000])), dim)
-            assert 1 <= ngs <= 64 and 1 <= wpb <= 16 and dw in (1, 2, 4, 8, 16, 32, 64)
+            assert 1 <= ngs <= 128 and 1 <= wpb <= 16 and dw in (1, 2, 4, 8, 16, 32, 64)
             assert need(dim, ngs, dw, wpb) <= 65536, (dim, n, nnz, ngs, dw, wpb)
             # the caller fixes the group size (a sweep): the rest still fits
             ngs2 = int(rng.choice([1, 2, 4, 8, 16, 32, 64]))
