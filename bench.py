@@ -8,7 +8,7 @@ relabelling, neighbor partitioning: Sec. 4.1 / 5.1) happens before the timed reg
 reported separately, as the paper does.  Prints ONE JSON line on stdout.
 
 Other configurations (--config 1..4) run the remaining workloads; --ngs/--dw/--wpb/--flags give
-the parameter sweeps, --renumber applies gnn_reorder first.
+the parameter sweeps; --no-renumber keeps the generated ids, --renumber renumbers whatever the rule says.
 """
 from __future__ import annotations
 
@@ -69,7 +69,9 @@ def main():
     ap.add_argument("--dw", type=int, default=0)
     ap.add_argument("--wpb", type=int, default=0)
     ap.add_argument("--flags", type=int, default=0, help="extra GNN_FLAG_* bits for the aggregation")
-    ap.add_argument("--renumber", action="store_true", help="apply gnn_reorder (forced) before the run")
+    ap.add_argument("--renumber", action="store_true",
+                    help="apply gnn_reorder whatever its rule says (default: the rule of Sec. 5.1 decides)")
+    ap.add_argument("--no-renumber", action="store_true", help="keep the generated ids (no gnn_reorder)")
     ap.add_argument("--renumber-device", action="store_true",
                     help="renumber on the GPU instead: gnn_reorder_device + gnn_apply_perm_csr_device (round-based schedule)")
     ap.add_argument("--hidden", type=int, default=0, help="override the hidden dimension of the model (sweep)")
@@ -126,10 +128,17 @@ def main():
         ew_h = gnn.gnn_gcn_norm(rp_h, ci_h)
         prep["gcn_norm_host_ms"] = (time.perf_counter() - t0) * 1e3
     perm = None
-    if args.renumber:
+    # One-time preparation, as in the paper's pipeline: community-aware renumbering when the rule of
+    # Sec. 5.1 (sqrt(AES) > floor(sqrt(N)/100)) asks for it.  --renumber forces it, --no-renumber skips it.
+    if not args.no_renumber and not args.renumber_device:
         t0 = time.perf_counter()
-        perm, iperm, _, _ = gnn.gnn_reorder(rp_h, ci_h, force=True)
+        perm, iperm, _, did = gnn.gnn_reorder(rp_h, ci_h, force=args.renumber)
         prep["reorder_host_ms"] = (time.perf_counter() - t0) * 1e3
+        prep["reorder_rule_says"] = bool(did)
+        args.renumber = bool(did)
+        if not did:
+            perm = None
+    if args.renumber and perm is not None:
         t0 = time.perf_counter()
         if ew_h is None:
             rp_h, ci_h = gnn.gnn_apply_perm_csr(rp_h, ci_h, perm)

@@ -216,24 +216,38 @@ void decide_defaults(int32_t n, int64_t nnz, int32_t max_degree, int32_t dim, in
 {
     const double avg = n > 0 ? (double)nnz / (double)n : 0.0;
     const bool auto_dw = *dw <= 0;
-    // dimension workers: lanes per neighbor row.  Each lane moves `vec` floats per load and owns up
-    // to 4 chunks of the row.  Measured on MI355X (sweeps over dw at Dim 16 ... 256 on five kinds of
-    // graphs): the best team is the one whose single load instruction covers exactly one 128-byte cache
-    // line of the row -- 8 lanes of 16 bytes -- so that a wavefront requests 8 distinct lines per
-    // instruction and a lane keeps several chunks x neighbours in flight; wider teams (one chunk per lane)
-    // were 5-11 % slower at Dim 128-256 and narrower ones (half a line per load) 6-14 % slower.  Rows
-    // shorter than a line get the power of two that covers them; rows longer than 3 lines widen the team
-    // until 3 chunks suffice.  A row of at most 4 neighbors fills a lane's loads in flight only if the
-    // lane takes two chunks (measured on batches of small graphs: 25 % faster at Dim 64), so a one-chunk
-    // team is halved there.
+    // dimension workers: lanes per neighbor row.  Each lane moves `vec` floats per load and owns the
+    // chunks of the row that lie dw lanes apart.  Measured on MI355X (sweeps over dw at Dim 3 ... 256 on
+    // five kinds of graphs), in this order of importance:
+    //   * no idle lane-slots: dw * chunks should not exceed the row (Dim 22 = 11 loads of 8 bytes: 4 lanes x 3
+    //     chunks beat 16 lanes x 1 chunk by 10 % of a model pass once the graph is renumbered);
+    //   * at most three chunks per lane (four leave only two neighbours in flight: 7 % slower at Dim 128);
+    //   * among equals, the team whose single load covers one 128-byte line of the row (8 lanes of 16 bytes),
+    //     so that a wavefront requests 8 distinct lines per instruction: one-chunk teams of 16-64 lanes were
+    //     5-11 % slower at Dim 128-256, half-line teams 6-14 % slower;
+    //   * at least 4 lanes (or the whole row) per team, so that a wavefront does not carry more than 16 teams.
+    // A row of at most 4 neighbors fills a lane's loads in flight only if the lane takes two chunks
+    // (measured on batches of small graphs: 25 % faster at Dim 64), so a one-chunk team is halved there.
     if (auto_dw) {
         const int units = (dim + vec - 1) / vec;
         const int line_lanes = 128 / (4 * vec);
-        int d = 1;
-        while (d < units && d < line_lanes) d *= 2;
-        while (d < 64 && (units + d - 1) / d > 3) d *= 2;  // (four chunks leave only two neighbours in flight: 7 % slower at Dim 128)
-        if (avg <= 4.0 && d > 1 && (units + d - 1) / d == 1 && units >= 2) d /= 2;
-        *dw = d;
+        int dmin = 1;
+        while (dmin < units && dmin < 4) dmin *= 2;
+        int best = 64, best_slots = 1 << 30, best_dist = 1 << 30;
+        for (int d = dmin; d <= 64; d *= 2) {
+            const int chunks = (units + d - 1) / d;
+            if (chunks > 3 && d < 64) continue;
+            const int slots = d * chunks;
+            int dist = 0;
+            for (int a = d, b = line_lanes; a != b; (a < b ? a *= 2 : b *= 2)) ++dist;
+            if (slots < best_slots || (slots == best_slots && dist < best_dist)) {
+                best = d;
+                best_slots = slots;
+                best_dist = dist;
+            }
+        }
+        if (avg <= 4.0 && best > 1 && (units + best - 1) / best == 1 && units >= 2) best /= 2;
+        *dw = best;
     }
     // neighbor-group size, from the graph alone so that one partition serves every layer of a
     // model.  Time ~ (#groups * per-group cost) + (#entries * per-row cost): bigger groups mean
