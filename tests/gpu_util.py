@@ -67,6 +67,7 @@ class LayerChain:
         self.ref = X           # the oracle's own chain
         self.done = 0
         self.errors = []
+        self.strict_errors = []
 
     def _oracle_layer(self, H, l, want_abs):
         relu = l != len(self.Ws) - 1
@@ -86,9 +87,16 @@ class LayerChain:
         torch.cuda.synchronize()
         gnn.gnn_workspace_status(self.ws)
         gpu_in = self.gpu.cpu().numpy()
-        ref_tf, scale = self._oracle_layer(gpu_in, l, True)
+        ref_tf, scale, scale_last = self._oracle_layer(gpu_in, l, "both")
         got = out.cpu().numpy()
         self.errors.append(assert_parity(got, ref_tf, scale, f"{self.name} layer {l + 1} (same inputs)"))
+        # reported, not gated: the same componentwise error against the stricter scale of the layer's last
+        # operation alone (it leaves the rounding of the first operation's result uncovered)
+        from util import parity_errors
+        strict = parity_errors(got, ref_tf, scale_last)[1]
+        self.strict_errors.append(strict)
+        print(f"{self.name} layer {l + 1}: normwise {self.errors[-1][0]:.2e}, guarded {self.errors[-1][1]:.2e}, "
+              f"guarded against the last operation's scale alone {strict:.2e}", flush=True)
         self.ref = ref_tf if l == 0 else self._oracle_layer(self.ref, l, False)
         self.gpu = out
         self.done += 1
