@@ -93,10 +93,6 @@ __global__ __launch_bounds__(256) void k_agg_epilogue_spanning(AggParams p)
     }
 }
 
-#ifndef GNN_XCD_RUN
-#define GNN_XCD_RUN 32
-#endif
-constexpr int kXcdRun = GNN_XCD_RUN;  // consecutive tiles that stay on one XCD
 
 // The gather of one team (Sec. 4.2: the team's lanes are the dimension workers of one neighbor group):
 // for the ITER chunks that start at chunk c0, acc[c][:] = reduce over the group's staged entries of
@@ -706,11 +702,13 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     if (fuse) fuse->done = false;
     const double avg_row = n > 0 ? (double)nnz / (double)n : 0.0;
     const bool kernel_chosen = (flags & GNN_FLAG_XCD_RUNS) != 0;
-    // (measured: one launch per layer wins while the layer's input stays in the 256 MB memory-side cache,
-    // -20 % on 44 k nodes, -2 % on 440 k; on 1.9 M nodes the two separate kernels are 7 % faster)
+    // (measured: the wave-tile form of the fused layer wins on short rows at every size, -20 % of a model pass
+    // on 44 k nodes and on 1.9 M; the block-tile form, which serves the shapes the other does not cover, only
+    // while the layer's input stays in the 256 MB memory-side cache)
     const bool small_enough = (double)n * (double)dim * 4.0 <= 160e6;
+    const bool wave_tiles_cover = fuse && gin_layer_fused_wave_tiles(p, vec, fuse->M);
     if (fuse && !atomic_flush && !(flags & GNN_FLAG_NO_FUSION) &&
-        ((flags & GNN_FLAG_FUSION) || (avg_row < 8.0 && small_enough && !kernel_chosen))) {
+        ((flags & GNN_FLAG_FUSION) || (avg_row < 8.0 && (small_enough || wave_tiles_cover) && !kernel_chosen))) {
         // large tiles (up to 64 groups) amortise the copy of W every block makes
         int wpb_f = wpb;
         if (auto_wpb) {
@@ -719,6 +717,11 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
         }
         AggParams pf = p;
         pf.T = wpb_f * (64 >> dwl_log2);
+        const bool wave_tiles = wave_tiles_cover;
+        if (wave_tiles) {
+            pf.T = 16;
+            wpb_f = 8;
+        }
         const int32_t part_dim = fuse->M > dim ? fuse->M : dim;  // fused partial rows are M wide
         size_t off = L.total > ws_reserved ? L.total : ws_reserved;
         off = align_up(off);
@@ -730,8 +733,9 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
             if (rc < 0) return rc;
             if (rc == GNN_OK) {
                 const int it_f = p.iter_total < 4 ? p.iter_total : 4;
-                note_launch("k_gin_layer_fused", vec, it_f, unroll_of(vec, it_f), -1, false, true, op, pf.T, ngs, wpb_f, true,
-                            p.xcd_remap != 0);
+                if (wave_tiles) wpb_f = pf.extra_blocks;  // (the wave-tile form reports its waves per block there)
+                note_launch(wave_tiles ? "k_gin_layer_fused_w" : "k_gin_layer_fused", vec, it_f, unroll_of(vec, it_f),
+                            wave_tiles ? dwl_log2 : -1, false, true, op, pf.T, ngs, wpb_f, true, p.xcd_remap != 0);
                 if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));
                 fuse->done = true;
                 GNN_HIP_TRY(hipGetLastError());

@@ -12,6 +12,10 @@ namespace gnn {
 constexpr uint32_t kMagic = 0x474e4e41u;  // "GNNA"
 constexpr int kWaveSize = 64;
 constexpr int kNumXcd = 8;
+#ifndef GNN_XCD_RUN
+#define GNN_XCD_RUN 32
+#endif
+constexpr int kXcdRun = GNN_XCD_RUN;  // consecutive tiles that the aggregation kernels keep on one XCD
 constexpr int kMaxWavesPerBlock = 16;
 constexpr size_t kAlign = 256;
 constexpr size_t kMaxLdsBytes = 64 * 1024;  // per block, keeps several blocks per CU inside the 160 KB LDS

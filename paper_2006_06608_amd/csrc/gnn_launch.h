@@ -43,6 +43,9 @@ void launch_agg_epilogue_spanning(const AggParams &p, hipStream_t s);
 // kernel was launched, 1 when the shape does not qualify (nothing launched), < 0 on error.
 int try_gin_layer_fused(AggParams &p, int vec, int wpb, const float *W, const float *b, float *out, int M, int relu,
                         int64_t tiles_upper, hipStream_t s);
+// true if the wave-tile form of the fused layer covers the shape; the caller then sets p.T = 16 and sizes the
+// partial rows for tiles of 16 groups before it calls try_gin_layer_fused
+bool gin_layer_fused_wave_tiles(const AggParams &p, int vec, int M);
 
 // gnn_update.hip: out[n,M] = act(A[n,K] W[K,M] + b) on the MFMA units.
 int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b, int relu,

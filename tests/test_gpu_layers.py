@@ -307,6 +307,55 @@ def test_fusion_is_automatic_for_short_rows_and_can_be_switched_off():
     assert np.array_equal(outs[0].view(np.uint32), outs[3].view(np.uint32))  # the fused kernel is deterministic
 
 
+@pytest.mark.parametrize("K,dw,M", [(64, 8, 64), (64, 16, 64), (32, 8, 48), (32, 4, 16), (16, 4, 22)])
+@pytest.mark.parametrize("ngs", [1, 3, 16])
+def test_fused_wave_tiles_with_nodes_that_span_rounds_waves_and_tiles(K, dw, M, ngs):
+    """The wave-tile form of the fused GIN layer (a wave owns 16 groups, rows of the tile per target node,
+    ordered flush of the transformed partial rows in units of wave tiles) on a graph with hubs and with
+    groups so small that nodes continue from one round, wave and tile into the next.  X, W and b hold small
+    integers, so every sum is exact in fp32 whatever its order: the result must equal the oracle bit for
+    bit -- a partial row that was stale, counted twice or left out could not hide in rounding -- and so must
+    a second run."""
+    g = config_graph(5, shrink=64)
+    rng = np.random.default_rng(K * 1000 + M * 10 + ngs)
+    X = rng.integers(-3, 4, size=(g.n, K)).astype(np.float32)
+    W = rng.integers(-2, 3, size=(K, M)).astype(np.float32)
+    b = rng.integers(-4, 5, size=M).astype(np.float32)
+    ref = oracle.gin_layer(g.rowptr, g.colidx, 1.0, X, W, b, True)
+    G = DeviceGraph(g.rowptr, g.colidx)
+    ws = gnn.alloc_workspace(G.n, G.nnz, max(K, M), ngs)
+    outs = []
+    for _ in range(2):
+        out = torch.full((g.n, M), float("nan"), device="cuda")
+        gnn.gnn_layer_forward(gnn.GNN_GIN, G.n, G.nnz, G.rowptr, G.colidx, None, 1.0, dev(X), K, dev(W), dev(b), M, True, out,
+                              ngs, dw, 0, gnn.GNN_FLAG_FUSION, ws)
+        torch.cuda.synchronize()
+        gnn.gnn_workspace_status(ws)
+        assert gnn.gnn_bench_last_aggregation().startswith("k_gin_layer_fused_w"), gnn.gnn_bench_last_aggregation()
+        outs.append(out.cpu().numpy())
+    assert np.array_equal(outs[0], ref.astype(np.float32)), np.abs(outs[0] - ref).max()
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+
+
+def test_fused_layer_takes_the_block_tile_form_where_the_wave_tile_form_does_not_apply():
+    # rows of 96 floats, and groups of more entries than a team keeps in registers
+    g = config_graph(3, shrink=8)
+    G = DeviceGraph(g.rowptr, g.colidx)
+    for K, ngs in ((96, 16), (64, 64)):
+        X = features(g.n, K, seed=K)
+        W = glorot(K, 32, seed=ngs)
+        ref, scale = oracle.gin_layer(g.rowptr, g.colidx, 0.0, X, W, None, False, want_abs=True)
+        ws = gnn.alloc_workspace(G.n, G.nnz, K, ngs)
+        out = torch.full((g.n, 32), float("nan"), device="cuda")
+        gnn.gnn_layer_forward(gnn.GNN_GIN, G.n, G.nnz, G.rowptr, G.colidx, None, 0.0, dev(X), K, dev(W), None, 32, False, out,
+                              ngs, 0, 0, gnn.GNN_FLAG_FUSION, ws)
+        torch.cuda.synchronize()
+        gnn.gnn_workspace_status(ws)
+        name = gnn.gnn_bench_last_aggregation()
+        assert name.startswith("k_gin_layer_fused<"), name
+        assert_parity(out.cpu().numpy(), ref, scale, f"block-tile fused layer K {K} ngs {ngs}")
+
+
 @pytest.mark.parametrize("out_dim", [1, 2, 3, 5, 6, 7, 22, 33, 70])
 @pytest.mark.parametrize("flags", [0, gnn.GNN_FLAG_ATOMIC_FLUSH, gnn.GNN_FLAG_DETERMINISTIC, gnn.GNN_FLAG_XCD_RUNS,
                                    gnn.GNN_FLAG_NO_BLOCK_OPT])
