@@ -82,13 +82,16 @@ extern "C" {
                                        always used.  Not combinable with GNN_FLAG_NO_BLOCK_OPT or
                                        GNN_FLAG_ATOMIC_FLUSH (GNN_EINVAL) */
 #define GNN_FLAG_FUSION 64u         /* gnn_layer_forward / gnn_model_forward, GNN_GIN: fuse the Update GEMM into
-                                       the aggregation kernel where the shape allows (in_dim <= 128 and a
-                                       multiple of 4, out_dim <= 64, <= 8 waves per block, a multiple of
-                                       ceil(out_dim/16), workspace with room for the ordered flush).  The
-                                       library fuses by itself when the mean row has fewer than 8 entries and
-                                       the layer's input is at most 160 MB (batches of small graphs: one launch
-                                       per layer, -20 %); on graphs with long rows and on inputs beyond the
-                                       memory-side cache the two separate kernels are faster, hence the flag */
+                                       the aggregation kernel where the shape allows (out_dim <= 64, workspace
+                                       with room for the ordered flush; in_dim of 16, 32 or 64 with groups of
+                                       at most 4 x dw entries takes the wave-tile form, which ignores
+                                       waves_per_block; other in_dim <= 128 that are multiples of 4 take the
+                                       block-tile form with <= 8 waves per block, a multiple of
+                                       ceil(out_dim/16)).  The library fuses by itself when the mean row has
+                                       fewer than 8 entries (batches of small graphs: -20 % of a model pass)
+                                       and either the wave-tile form applies or the layer's input is at most
+                                       160 MB; on graphs with long rows the fused layer is as fast as the two
+                                       separate kernels at best, hence the flag */
 #define GNN_FLAG_NO_FUSION 512u     /* never fuse */
 #define GNN_FLAG_ATOMIC_FLUSH 128u  /* always finish nodes that span blocks the way Sec. 5.2 describes: the
                                        leader adds the block's partial row to global memory with one float

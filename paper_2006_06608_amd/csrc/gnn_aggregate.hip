@@ -32,6 +32,10 @@
 #include "gnn_bench.h"
 #include "gnn_launch.h"
 
+#ifndef GNN_EMPTY_FIRST
+#define GNN_EMPTY_FIRST 1
+#endif
+
 namespace gnn {
 
 // Rows the main kernel will not store plainly: rows without entries get their final value, rows
@@ -236,19 +240,30 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
     int *s_more = s_last + kMaxWavesPerBlock;                     // [16]: the node continues behind this wave
     int *s_list = s_more + kMaxWavesPerBlock;                     // [nw][64]
 
+#if GNN_EMPTY_FIRST
+    if ((int)blockIdx.x < p.extra_blocks) {
+        // the first blocks of the grid: rows without entries (independent of every tile; a multiple of the
+        // number of XCDs, so that block b - extra_blocks still runs on XCD b mod 8)
+        write_empty_rows<VEC, SELF>(p, (int64_t)blockIdx.x * nw + wave, (int64_t)p.extra_blocks * nw, s_list + wave * 64);
+        return;
+    }
+    const int64_t bid = (int64_t)blockIdx.x - p.extra_blocks;
+#else
     if ((int64_t)blockIdx.x >= p.tile_blocks) {
         // blocks appended to the grid: rows without entries (independent of every tile)
         const int64_t eb = (int64_t)blockIdx.x - p.tile_blocks;
         write_empty_rows<VEC, SELF>(p, eb * nw + wave, (int64_t)p.extra_blocks * nw, s_list + wave * 64);
         return;
     }
-    int64_t tile = blockIdx.x;
+    const int64_t bid = blockIdx.x;
+#endif
+    int64_t tile = bid;
     if (p.xcd_remap) {
         // Blocks are dealt to the eight XCDs round-robin by index.  Give every XCD runs of kXcdRun
         // consecutive tiles (neighbouring node ids, hence shared neighbours after renumbering, meet
         // in one L2) while the runs themselves still interleave over the XCDs, which keeps the
         // load balanced.
-        const int64_t x = blockIdx.x % kNumXcd, q = blockIdx.x / kNumXcd;
+        const int64_t x = bid % kNumXcd, q = bid / kNumXcd;
         tile = ((q / kXcdRun) * kNumXcd + x) * kXcdRun + q % kXcdRun;
     }
     const int64_t num_ng = hv.num_ng;
@@ -778,6 +793,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     const int64_t nchunks = ((int64_t)n + 63) / 64;
     int64_t extra = (nchunks + (int64_t)wpb * 4 - 1) / ((int64_t)wpb * 4);
     if (extra > 8192) extra = 8192;
+    extra = (extra + kNumXcd - 1) / kNumXcd * kNumXcd;
     p.do_empty = 1;
     p.tile_blocks = grid;
     p.extra_blocks = (int)extra;

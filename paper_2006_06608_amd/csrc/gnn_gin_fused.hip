@@ -1,6 +1,7 @@
-// GIN layer with the Update fused into the Aggregation, built on the general aggregation kernel:
-// out = act(((1+eps) X + sum_N X) W + b) in one launch (an MI355X addition; the paper runs the two
-// phases as separate kernels).
+// GIN layer with the Update fused into the Aggregation: out = act(((1+eps) X + sum_N X) W + b) in one
+// launch (an MI355X addition; the paper runs the two phases as separate kernels).  Two forms: the
+// wave-tile form (k_gin_layer_fused_w, further down; rows of 16, 32 or 64 floats), in which every wave
+// works on its own, and the older block-tile form for the other shapes:
 //
 // A block aggregates its neighbor groups exactly as k_aggregate does, but every target node of the
 // block ends up as one row of an LDS tile A[T][K] (the Algorithm 1 slots, the waves adding in wave
@@ -430,10 +431,10 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
     int *sNode = reinterpret_cast<int *>(sW + K * LDW + (size_t)NW * 16 * LDA) + wave * 16;
     int *sFlag = sNode + NW * 16;  // bit 0: the row holds its node's first group, bit 1: its last group
 
-    // this thread's part of W (zero padded to 64 columns), requested now, written to LDS further down
+    // this thread's part of W (zero padded to 64 columns): requested early, written to LDS further down
     constexpr int NL = (K * 16 + NW * 64 - 1) / (NW * 64);
     float4 w4[NL];
-    {
+    auto load_w = [&]() {
         const bool vecw = (M % 4 == 0) && (((uintptr_t)fp.W & 15) == 0);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -451,7 +452,7 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
                 }
             }
         }
-    }
+    };
     auto store_w = [&]() {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -460,14 +461,23 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
         }
     };
 
-    if ((int64_t)blockIdx.x >= p.tile_blocks) {
-        // ---- rows without entries: act((1+eps) x W + b); every wave works alone, 16 such rows at a time
-        store_w();
-        __syncthreads();
+    if ((int)blockIdx.x < p.extra_blocks) {
+        // ---- the first blocks of the grid (a multiple of the number of XCDs): rows without entries,
+        // act((1+eps) x W + b); every wave works alone, 16 such rows at a time
         int *mylist = reinterpret_cast<int *>(sA);  // 64 ints of the wave's own tile area
         const int64_t nchunks = ((int64_t)p.n + 63) / 64;
-        const int64_t first_chunk = ((int64_t)blockIdx.x - p.tile_blocks) * NW + wave;
+        const int64_t first_chunk = (int64_t)blockIdx.x * NW + wave;
         const int64_t chunk_stride = (int64_t)p.extra_blocks * NW;
+        // a block whose nodes all have entries (every block, on many graphs) leaves without touching W
+        int any = 0;
+        for (int64_t c = first_chunk; c < nchunks; c += chunk_stride) {
+            const int64_t v = c * 64 + lane;
+            any |= (v < p.n && p.ngptr[v] == p.ngptr[v + 1]) ? 1 : 0;
+        }
+        if (!__syncthreads_or(any)) return;
+        load_w();
+        store_w();
+        __syncthreads();
         for (int64_t c = first_chunk; c < nchunks; c += chunk_stride) {
             const int64_t v = c * 64 + lane;
             const bool empty = v < p.n && p.ngptr[v] == p.ngptr[v + 1];
@@ -514,9 +524,11 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
         return;
     }
 
-    int64_t btile = blockIdx.x;
+    load_w();
+    const int64_t bid = (int64_t)blockIdx.x - p.extra_blocks;
+    int64_t btile = bid;
     if (p.xcd_remap) {
-        const int64_t x = blockIdx.x % kNumXcd, q = blockIdx.x / kNumXcd;
+        const int64_t x = bid % kNumXcd, q = bid / kNumXcd;
         btile = ((q / kXcdRun) * kNumXcd + x) * kXcdRun + q % kXcdRun;
     }
     const int64_t num_ng = hv.num_ng;
@@ -826,8 +838,10 @@ static int launch_gin_layer_fused_w(AggParams &p, const float *W, const float *b
     int64_t grid = (wave_tiles + nw - 1) / nw;
     if (p.xcd_remap) grid = (grid + kNumXcd * kXcdRun - 1) / (kNumXcd * kXcdRun) * (kNumXcd * kXcdRun);
     const int64_t nchunks = ((int64_t)p.n + 63) / 64;
-    int64_t extra = (nchunks + (int64_t)nw * 8 - 1) / ((int64_t)nw * 8);
-    if (extra > 4096) extra = 4096;
+    // rows without entries: the first blocks of the grid, each wave taking about two 64-node chunks
+    int64_t extra = (nchunks + (int64_t)nw * 2 - 1) / ((int64_t)nw * 2);
+    if (extra > 8192) extra = 8192;
+    extra = (extra + kNumXcd - 1) / kNumXcd * kNumXcd;
     if (grid + extra >= ((int64_t)1 << 31)) return GNN_ELIMIT;
     FusedParams fp;
     fp.a = p;
