@@ -734,7 +734,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
         pf.T = wpb_f * (64 >> dwl_log2);
         const bool wave_tiles = wave_tiles_cover;
         if (wave_tiles) {
-            pf.T = 16;
+            pf.T = kFusedWaveTile;
             wpb_f = 8;
         }
         const int32_t part_dim = fuse->M > dim ? fuse->M : dim;  // fused partial rows are M wide

@@ -414,11 +414,12 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
     }
     constexpr int VEC = 4;
     constexpr int dwl = 1 << DL, G = 64 >> DL;  // lanes per team, teams per round
-    constexpr int R = 16 / G;                   // rounds
+    constexpr int TILE = kFusedWaveTile;        // groups per wave
+    constexpr int R = TILE / G;                 // rounds
     constexpr int K = ITER * dwl * VEC;
     constexpr int NS = K / 16;
     constexpr int LDA = K + 4, LDW = 68;
-    static_assert(G <= 16 && K % 16 == 0 && U <= dwl * J, "shape not covered");
+    static_assert(G <= TILE && K % 16 == 0 && U <= dwl * J, "shape not covered");
     const int M = fp.M, ct = fp.ct;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tlane = lane & (dwl - 1), team = lane >> DL, tbase = lane & ~(dwl - 1);
@@ -427,8 +428,8 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
     // LDS: sW[K][LDW] | sA[NW][16][LDA] | sNode[NW][16] | sFlag[NW][16]   (blocks that serve rows without
     // entries use the tile area for their lists)
     float *sW = reinterpret_cast<float *>(smem);
-    float *sA = sW + K * LDW + (size_t)wave * 16 * LDA;
-    int *sNode = reinterpret_cast<int *>(sW + K * LDW + (size_t)NW * 16 * LDA) + wave * 16;
+    float *sA = sW + K * LDW + (size_t)wave * TILE * LDA;
+    int *sNode = reinterpret_cast<int *>(sW + K * LDW + (size_t)NW * TILE * LDA) + wave * 16;
     int *sFlag = sNode + NW * 16;  // bit 0: the row holds its node's first group, bit 1: its last group
 
     // this thread's part of W (zero padded to 64 columns): requested early, written to LDS further down
@@ -532,9 +533,9 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
         btile = ((q / kXcdRun) * kNumXcd + x) * kXcdRun + q % kXcdRun;
     }
     const int64_t num_ng = hv.num_ng;
-    if (btile * (NW * 16) >= num_ng) return;  // (the whole block: the grid is sized from an upper bound)
+    if (btile * (NW * TILE) >= num_ng) return;  // (the whole block: the grid is sized from an upper bound)
     const int64_t wtile = btile * NW + wave;  // the wave's tile: groups [16 wtile, 16 wtile + 16)
-    const int64_t g0 = wtile * 16;
+    const int64_t g0 = wtile * TILE;
 
     // tuples, then own rows and column indices of all rounds: two round trips in front of the gather
     NgEntry e[R];
@@ -737,13 +738,13 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
             if (lane == 0) arrived = atomicAdd(&p.cnt[node], 1);
             arrived = __shfl(arrived, 0);
             const int gfirst = p.ngptr[node], gend = p.ngptr[node + 1];
-            const int64_t b0 = gfirst / 16, b1 = (gend - 1) / 16;
+            const int64_t b0 = gfirst / TILE, b1 = (gend - 1) / TILE;
             if (arrived != (int)(b1 - b0)) continue;
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
             if (lane == 0) p.cnt[node] = 0;
             if (lane < M) {
                 // in its first tile the node is the tile's first node only if it starts the tile
-                float sum = __hip_atomic_load(p.part_rows + ((size_t)b0 * 2 + (gfirst % 16 == 0 ? 0 : 1)) * M + lane,
+                float sum = __hip_atomic_load(p.part_rows + ((size_t)b0 * 2 + (gfirst % TILE == 0 ? 0 : 1)) * M + lane,
                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 for (int64_t b = b0 + 1; b <= b1; b += 4) {
                     float tq[4];
@@ -786,7 +787,6 @@ static const void *fused_fn(int iter, int ns)
 }
 
 // ---- the wave-tile form ----
-constexpr int kFusedWaveTile = 16;  // groups per wave
 // Waves per block (they share the copy of W): 8 on large graphs, where the copy is what limits the number of
 // resident waves; 4 when the whole grid is resident at once anyway, so that more blocks spread over the CUs.
 constexpr int kFusedWavesLarge = 8, kFusedWavesSmall = 4;
@@ -833,7 +833,7 @@ static int launch_gin_layer_fused_w(AggParams &p, const float *W, const float *b
     const int nw = wave_tiles <= kFusedSmallGrid ? kFusedWavesSmall : kFusedWavesLarge;
     const void *fn = fused_w_kernel(p.dwl_log2, p.iter_total, (p.ngs + dwl - 1) / dwl, nw);
     if (!fn || !p.part_rows || ((uintptr_t)W | (uintptr_t)out) % 4 != 0) return 1;
-    const size_t lds = ((size_t)K * 68 + (size_t)nw * 16 * (K + 4) + (size_t)nw * 32) * 4;
+    const size_t lds = ((size_t)K * 68 + (size_t)nw * kFusedWaveTile * (K + 4) + (size_t)nw * 32) * 4;
     if (lds > kMaxLdsBytes) return 1;
     int64_t grid = (wave_tiles + nw - 1) / nw;
     if (p.xcd_remap) grid = (grid + kNumXcd * kXcdRun - 1) / (kNumXcd * kXcdRun) * (kNumXcd * kXcdRun);

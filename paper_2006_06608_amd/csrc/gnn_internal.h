@@ -93,6 +93,10 @@ inline WsLayout ws_layout(int32_t n, int64_t nnz, int32_t max_dim, int32_t ngs_f
 // scratch memory behind the caller's own use of the workspace.  The workspace-size functions allow
 // for blocks of at least kPartMinTile groups.
 constexpr int kPartMinTile = 16;
+// groups that one wave of the wave-tile form of the fused GIN layer serves (its unit of the ordered flush)
+// (8 measured slower: half-empty MFMA tiles double the time on the matrix units, which does not hide)
+constexpr int kFusedWaveTile = 16;
+static_assert(kFusedWaveTile >= kPartMinTile, "the workspace allows partial rows for tiles of kPartMinTile groups");
 
 inline size_t part_rows_bytes(int64_t ng_capacity, int tile, int32_t dim)
 {
