@@ -326,8 +326,8 @@ def main():
         agg_dims = [head_dim]
     elif kind == "gin":
         agg_dims = [dims[0]] * layers
-    else:  # GCN aggregates at the output width, or at the input width of a widening layer on request
-        narrow = bool(args.flags & gnn.GNN_FLAG_GCN_NARROW_FIRST)
+    else:  # GCN aggregates at the narrower of a layer's two widths (at the output width on request)
+        narrow = not (args.flags & gnn.GNN_FLAG_GCN_UPDATE_FIRST)
         agg_dims = [dims[l] if narrow and dims[l] < dims[l + 1] else dims[l + 1] for l in range(layers)]
     edges_dim_step = float(nnz) * float(sum(agg_dims))
     value = edges_dim_step / (ms_per_step * 1e-3)

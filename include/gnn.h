@@ -97,12 +97,14 @@ extern "C" {
                                        leader adds the block's partial row to global memory with one float
                                        atomic per element (rows zeroed by a kernel that runs first, bias and
                                        activation of those rows by a kernel that runs last) */
-#define GNN_FLAG_GCN_NARROW_FIRST 256u /* gnn_layer_forward / gnn_model_forward, GNN_GCN: a layer whose output
-                                       is wider than its input aggregates first, at the input width, and
-                                       updates afterwards: act((A_hat X) W + b) instead of act(A_hat (X W) + b).
-                                       Same value up to rounding (Sec. 3.1 orders the two phases so that the
-                                       aggregation runs at the smaller width); off by default because it
-                                       moves the points where intermediate results are rounded to fp32 */
+#define GNN_FLAG_GCN_NARROW_FIRST 256u /* accepted and ignored: it asked for what is now the default (see below) */
+#define GNN_FLAG_GCN_UPDATE_FIRST 1024u /* gnn_layer_forward / gnn_model_forward, GNN_GCN.  Sec. 3.1 orders the two
+                                       phases of a GCN layer so that the aggregation runs at the smaller width:
+                                       Update first when the layer narrows.  A layer whose output is wider than
+                                       its input therefore aggregates first, at the input width, and updates
+                                       afterwards: act((A_hat X) W + b) instead of act(A_hat (X W) + b), the same
+                                       value up to rounding.  This flag keeps Update-then-Aggregation for such a
+                                       layer too (the literal order of the paper's GCN) */
 
 /* ================================================================================== */
 /* HOST-side preparation                                                              */

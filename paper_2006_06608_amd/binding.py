@@ -10,7 +10,7 @@ import numpy as np
 __all__ = [
     "GnnError", "lib_path", "load", "exported_symbols",
     "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_XCD_RUNS", "GNN_FLAG_NO_PIPELINE",
-    "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_FLAG_NO_FUSION", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
+    "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_FLAG_GCN_UPDATE_FIRST", "GNN_FLAG_NO_FUSION", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
     "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall", "AggregateCall",
     "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
     "gnn_bench_stream_read", "gnn_bench_gather_rows", "gnn_csr_transpose_device", "gnn_bench_last_aggregation",
@@ -28,6 +28,7 @@ GNN_FLAG_DETERMINISTIC = 32
 GNN_FLAG_FUSION = 64
 GNN_FLAG_ATOMIC_FLUSH = 128
 GNN_FLAG_GCN_NARROW_FIRST = 256
+GNN_FLAG_GCN_UPDATE_FIRST = 1024
 GNN_FLAG_NO_FUSION = 512
 GNN_REDUCE_SUM, GNN_REDUCE_MAX, GNN_REDUCE_MIN, GNN_REDUCE_MEAN = 0, 1, 2, 3
 

@@ -248,7 +248,7 @@ def test_model_forward_equals_the_layer_by_layer_chain_and_the_oracle(cfg, shrin
         gnn.gnn_model_forward(kind, G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), dims, Wd, bd, out, workspace=ws[:4096])
 
 
-def test_widening_gcn_layer_may_aggregate_first():
+def test_widening_gcn_layer_aggregates_first_unless_told_otherwise():
     g = config_graph(4, shrink=16)
     ew = oracle.gcn_norm(g.rowptr, g.colidx)
     G = DeviceGraph(g.rowptr, g.colidx, ew)
@@ -258,7 +258,7 @@ def test_widening_gcn_layer_may_aggregate_first():
     ref, scale = oracle.gcn_layer(g.rowptr, g.colidx, ew, X, W, b, True, want_abs=True)
     ws = gnn.alloc_workspace(G.n, G.nnz, 22, 0)
     outs = {}
-    for flags in (0, gnn.GNN_FLAG_GCN_NARROW_FIRST):
+    for flags in (0, gnn.GNN_FLAG_GCN_UPDATE_FIRST):
         out = torch.full((G.n, 22), float("nan"), device="cuda")
         gnn.gnn_layer_forward(gnn.GNN_GCN, G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), 16, dev(W), dev(b), 22, True,
                               out, 0, 0, 0, flags, ws)
@@ -271,7 +271,7 @@ def test_widening_gcn_layer_may_aggregate_first():
     W2 = glorot(22, 16, seed=94)
     X2 = features(g.n, 22, seed=95)
     res = []
-    for flags in (0, gnn.GNN_FLAG_GCN_NARROW_FIRST):
+    for flags in (0, gnn.GNN_FLAG_GCN_UPDATE_FIRST):
         out = torch.full((G.n, 16), float("nan"), device="cuda")
         gnn.gnn_layer_forward(gnn.GNN_GCN, G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X2), 22, dev(W2), None, 16, False,
                               out, 0, 0, 0, flags, ws)
@@ -391,14 +391,15 @@ def test_gcn_layer_in_a_workspace_without_room_for_partial_rows():
     ref, ab = oracle.gcn_layer(g.rowptr, g.colidx, ew, X, W, None, False, want_abs=True)
     out = torch.full((g.n, 22), float("nan"), device="cuda")
     full = gnn.alloc_workspace(g.n, g.nnz, 22, 16)
-    # keep the intermediate, drop the partial rows: rows that span blocks are finished with atomics
+    # keep the intermediate (Update first: 22 floats per node), drop the partial rows: rows that span blocks
+    # are finished with atomics
     tight = full[: gnn.gnn_workspace_bytes(g.n, g.nnz, 0, 16) + ((g.n * 22 * 4 + 255) // 256) * 256]
     assert tight.numel() < full.numel()
     with pytest.raises(gnn.GnnError):
         gnn.gnn_layer_forward(gnn.GNN_GCN, g.n, g.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), 16, dev(W), None, 22, False,
-                              out, 16, 0, 0, gnn.GNN_FLAG_DETERMINISTIC, tight)
+                              out, 16, 0, 0, gnn.GNN_FLAG_DETERMINISTIC | gnn.GNN_FLAG_GCN_UPDATE_FIRST, tight)
     gnn.gnn_layer_forward(gnn.GNN_GCN, g.n, g.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), 16, dev(W), None, 22, False, out,
-                          16, 0, 0, 0, tight)
+                          16, 0, 0, gnn.GNN_FLAG_GCN_UPDATE_FIRST, tight)
     torch.cuda.synchronize()
     gnn.gnn_workspace_status(tight)
     assert_parity(out.cpu().numpy(), ref, ab, "gcn layer 16->22, tight workspace")
