@@ -81,7 +81,7 @@ extern "C" {
                                        without room is an error (GNN_EWORKSPACE) and the general kernel is
                                        always used.  Not combinable with GNN_FLAG_NO_BLOCK_OPT or
                                        GNN_FLAG_ATOMIC_FLUSH (GNN_EINVAL) */
-#define GNN_FLAG_FUSION 64u         /* gnn_layer_forward / gnn_model_forward, GNN_GIN: fuse the Update GEMM into
+#define GNN_FLAG_FUSION 64u         /* gnn_layer_forward / gnn_model_forward: fuse the Update GEMM into
                                        the aggregation kernel where the shape allows (out_dim <= 64, workspace
                                        with room for the ordered flush; in_dim of 16, 32 or 64 with groups of
                                        at most 4 x dw entries takes the wave-tile form, which ignores
@@ -91,7 +91,9 @@ extern "C" {
                                        fewer than 8 entries (batches of small graphs: -20 % of a model pass)
                                        and either the wave-tile form applies or the layer's input is at most
                                        160 MB; on graphs with long rows the fused layer is as fast as the two
-                                       separate kernels at best, hence the flag */
+                                       separate kernels at best, hence the flag.  GNN_GCN: only a layer that
+                                       aggregates first (out_dim > in_dim) can be fused, in the wave-tile form
+                                       and only on request (measured slower than its two kernels) */
 #define GNN_FLAG_NO_FUSION 512u     /* never fuse */
 #define GNN_FLAG_ATOMIC_FLUSH 128u  /* always finish nodes that span blocks the way Sec. 5.2 describes: the
                                        leader adds the block's partial row to global memory with one float

@@ -402,7 +402,7 @@ void k_gin_layer_fused(FusedParams fp)
 // and take the ordered flush in units of wave tiles: transformed partial row (M floats; the product is
 // linear) to scratch, arrival counter, the wave that arrives last adds the partial rows in tile order.
 // No wave waits for another one except at the one barrier.
-template <int DL, int ITER, int U, int J, int NW>
+template <int DL, int ITER, int U, int J, int NW, bool WEIGHTED, bool SELF>
 __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -476,6 +476,15 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
             any |= (v < p.n && p.ngptr[v] == p.ngptr[v + 1]) ? 1 : 0;
         }
         if (!__syncthreads_or(any)) return;
+        if (!SELF) {
+            // no own-row term (GCN): a row without entries is act(b)
+            for (int64_t c = first_chunk; c < nchunks; c += chunk_stride) {
+                const int64_t v = c * 64 + lane;
+                if (v < p.n && p.ngptr[v] == p.ngptr[v + 1])
+                    for (int cc = 0; cc < M; ++cc) fp.out[(size_t)v * M + cc] = act_bias(0.0f, fp.b ? fp.b[cc] : 0.0f, fp.relu);
+            }
+            return;
+        }
         load_w();
         store_w();
         __syncthreads();
@@ -550,6 +559,7 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
     }
     const float *xb = p.X + (size_t)tlane * VEC;
     int cidx[R][J];
+    float cw[R][WEIGHTED ? J : 1];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int len = e[r].end - e[r].start;
@@ -557,6 +567,7 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
         for (int j = 0; j < J; ++j) {
             const int k = tlane + j * dwl;
             cidx[r][j] = k < len ? load_stream(&p.colidx[e[r].start + k]) : -1;
+            if (WEIGHTED) cw[r][j] = k < len ? load_stream(&p.ew[e[r].start + k]) : 0.0f;
         }
     }
     store_w();
@@ -574,16 +585,19 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
         for (int c = 0; c < ITER; ++c) {
 #pragma unroll
             for (int j = 0; j < VEC; ++j) acc[c][j] = xs[c][j] = 0.0f;
-            if (valid[r] && first) load_vec<VEC>(xs[c], xb + (size_t)(unsigned)e[r].node * (unsigned)K + c * dwl * VEC);
+            if (SELF && valid[r] && first)
+                load_vec<VEC>(xs[c], xb + (size_t)(unsigned)e[r].node * (unsigned)K + c * dwl * VEC);
         }
 #pragma unroll
         for (int jb = 0; jb < J * dwl / U; ++jb) {
             if (jb * U < len) {
                 int col[U];
+                float wgt[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int k = jb * U + u;  // compile-time: register k / dw, lane k % dw of the team
                     col[u] = __shfl(cidx[r][k >> DL], tbase + (k & (dwl - 1)));
+                    if (WEIGHTED) wgt[u] = __shfl(cw[r][k >> DL], tbase + (k & (dwl - 1)));
                 }
                 float v[U][ITER][VEC];
 #pragma unroll
@@ -603,14 +617,18 @@ __global__ __launch_bounds__(NW * 64) void k_gin_layer_fused_w(FusedParams fp)
 #pragma unroll
                     for (int c = 0; c < ITER; ++c)
 #pragma unroll
-                        for (int j = 0; j < VEC; ++j) acc[c][j] += v[u][c][j];
+                        for (int j = 0; j < VEC; ++j) {
+                            if (WEIGHTED) acc[c][j] = fmaf(wgt[u], v[u][c][j], acc[c][j]);
+                            else acc[c][j] += v[u][c][j];
+                        }
             }
         }
-
+        if (SELF) {
 #pragma unroll
-        for (int c = 0; c < ITER; ++c)
+            for (int c = 0; c < ITER; ++c)
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) acc[c][j] = fmaf(p.self_scale, xs[c][j], acc[c][j]);
+                for (int j = 0; j < VEC; ++j) acc[c][j] = fmaf(p.self_scale, xs[c][j], acc[c][j]);
+        }
 
         // Algorithm 1 inside the round: a team opens a segment when its target node differs from the team's
         // before it; the segment's first team collects the segment's sum and its "last group" flag
@@ -792,36 +810,44 @@ static const void *fused_fn(int iter, int ns)
 constexpr int kFusedWavesLarge = 8, kFusedWavesSmall = 4;
 constexpr int64_t kFusedSmallGrid = 4096;  // wave tiles
 
-template <int DL, int ITER, int U, int NW>
+template <int DL, int ITER, int U, int NW, bool WEIGHTED, bool SELF>
 static const void *fused_w_fn(int j)
 {
-    if (j <= 2) return (const void *)k_gin_layer_fused_w<DL, ITER, U, 2, NW>;
-    return (const void *)k_gin_layer_fused_w<DL, ITER, U, 4, NW>;
-}
-
-// Kernel for (team width 2^dl, chunks per lane, registers of indices per lane), or null if not covered.
-template <int NW>
-static const void *fused_w_kernel_nw(int dl, int iter, int j)
-{
-    if (j > 4) return nullptr;
-    if (dl == 3 && iter == 2) return fused_w_fn<3, 2, 4, NW>(j);  // K = 64, teams of 8
-    if (dl == 4 && iter == 1) return fused_w_fn<4, 1, 8, NW>(j);  // K = 64, teams of 16
-    if (dl == 3 && iter == 1) return fused_w_fn<3, 1, 8, NW>(j);  // K = 32, teams of 8
-    if (dl == 2 && iter == 2) return fused_w_fn<2, 2, 4, NW>(j);  // K = 32, teams of 4
-    if (dl == 2 && iter == 1) return fused_w_fn<2, 1, 8, NW>(j);  // K = 16, teams of 4
+    if (j <= 2) return (const void *)k_gin_layer_fused_w<DL, ITER, U, 2, NW, WEIGHTED, SELF>;
+    if (j <= 4) return (const void *)k_gin_layer_fused_w<DL, ITER, U, 4, NW, WEIGHTED, SELF>;
+    if constexpr (DL == 2 && ITER == 1) {  // rows of 16 floats: groups of up to 32 entries
+        if (j <= 8) return (const void *)k_gin_layer_fused_w<DL, ITER, U, 8, NW, WEIGHTED, SELF>;
+    }
     return nullptr;
 }
 
-static const void *fused_w_kernel(int dl, int iter, int j, int nw = kFusedWavesLarge)
+// Kernel for (team width 2^dl, chunks per lane, registers of indices per lane), or null if not covered.
+template <int NW, bool WEIGHTED, bool SELF>
+static const void *fused_w_kernel_nw(int dl, int iter, int j)
 {
-    return nw == kFusedWavesSmall ? fused_w_kernel_nw<kFusedWavesSmall>(dl, iter, j) : fused_w_kernel_nw<kFusedWavesLarge>(dl, iter, j);
+    if (dl == 3 && iter == 2) return fused_w_fn<3, 2, 4, NW, WEIGHTED, SELF>(j);  // K = 64, teams of 8
+    if (dl == 4 && iter == 1) return fused_w_fn<4, 1, 8, NW, WEIGHTED, SELF>(j);  // K = 64, teams of 16
+    if (dl == 3 && iter == 1) return fused_w_fn<3, 1, 8, NW, WEIGHTED, SELF>(j);  // K = 32, teams of 8
+    if (dl == 2 && iter == 2) return fused_w_fn<2, 2, 4, NW, WEIGHTED, SELF>(j);  // K = 32, teams of 4
+    if (dl == 2 && iter == 1) return fused_w_fn<2, 1, 8, NW, WEIGHTED, SELF>(j);  // K = 16, teams of 4
+    return nullptr;
+}
+
+// gcn: edge weights, no own-row term (Eq. 2); otherwise GIN: no weights, own row scaled by 1 + eps (Eq. 3)
+static const void *fused_w_kernel(bool gcn, int dl, int iter, int j, int nw = kFusedWavesLarge)
+{
+    if (gcn)
+        return nw == kFusedWavesSmall ? fused_w_kernel_nw<kFusedWavesSmall, true, false>(dl, iter, j)
+                                      : fused_w_kernel_nw<kFusedWavesLarge, true, false>(dl, iter, j);
+    return nw == kFusedWavesSmall ? fused_w_kernel_nw<kFusedWavesSmall, false, true>(dl, iter, j)
+                                  : fused_w_kernel_nw<kFusedWavesLarge, false, true>(dl, iter, j);
 }
 
 bool gin_layer_fused_wave_tiles(const AggParams &p, int vec, int M)
 {
     if (vec != 4 || !p.full_rows || M > 64 || M < 1) return false;
     const int dwl = 1 << p.dwl_log2;
-    return fused_w_kernel(p.dwl_log2, p.iter_total, (p.ngs + dwl - 1) / dwl) != nullptr;
+    return fused_w_kernel(p.ew != nullptr, p.dwl_log2, p.iter_total, (p.ngs + dwl - 1) / dwl) != nullptr;
 }
 
 static int launch_gin_layer_fused_w(AggParams &p, const float *W, const float *b, float *out, int M, int relu,
@@ -831,7 +857,7 @@ static int launch_gin_layer_fused_w(AggParams &p, const float *W, const float *b
     const int K = p.dim;
     const int64_t wave_tiles = (ng_cap + kFusedWaveTile - 1) / kFusedWaveTile;
     const int nw = wave_tiles <= kFusedSmallGrid ? kFusedWavesSmall : kFusedWavesLarge;
-    const void *fn = fused_w_kernel(p.dwl_log2, p.iter_total, (p.ngs + dwl - 1) / dwl, nw);
+    const void *fn = fused_w_kernel(p.ew != nullptr, p.dwl_log2, p.iter_total, (p.ngs + dwl - 1) / dwl, nw);
     if (!fn || !p.part_rows || ((uintptr_t)W | (uintptr_t)out) % 4 != 0) return 1;
     const size_t lds = ((size_t)K * 68 + (size_t)nw * kFusedWaveTile * (K + 4) + (size_t)nw * 32) * 4;
     if (lds > kMaxLdsBytes) return 1;
@@ -875,6 +901,7 @@ int try_gin_layer_fused(AggParams &p, int vec, int wpb, const float *W, const fl
         }
         return rc;
     }
+    if (p.ew) return 1;  // (the block-tile form has no edge weights)
     const int K = p.dim;
     const int ns = K <= 16 ? 1 : (K <= 32 ? 2 : (K <= 64 ? 4 : (K <= 128 ? 8 : 0)));
     const int T = p.T;

@@ -719,9 +719,12 @@ int gnn_layer_forward_timed(int kind, int32_t n, int64_t nnz, const int32_t *row
     float *tmp = (float *)((char *)workspace + L.tmp);
     flags &= ~(GNN_FLAG_GCN_NARROW_FIRST | GNN_FLAG_GCN_UPDATE_FIRST);
     if (narrow_first) {
+        // (the Update may be fused into the aggregation, as for GIN)
+        FuseSpec fuse = {W, b, out, out_dim, relu, false};
         int rc = aggregate_impl(false, 0.0f, n, nnz, rowptr, colidx, ew, X, tmp, in_dim, ngs_r, dw, waves_per_block, flags,
-                                nullptr, 0, workspace, workspace_bytes, L.total, s, ev0, ev1, nullptr);
+                                nullptr, 0, workspace, workspace_bytes, L.total, s, ev0, ev1, &fuse);
         if (rc != GNN_OK) return rc;
+        if (fuse.done) return GNN_OK;
         return update_gemm_impl(n, in_dim, out_dim, tmp, W, b, relu, out, s);
     }
     if (kind == GNN_GCN) {

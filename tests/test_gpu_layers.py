@@ -337,6 +337,49 @@ def test_fused_wave_tiles_with_nodes_that_span_rounds_waves_and_tiles(K, dw, M, 
     assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
 
 
+@pytest.mark.parametrize("K,M,ngs", [(16, 22, 32), (16, 22, 5), (32, 48, 16), (16, 64, 8), (64, 70, 32)])
+def test_fused_gcn_layer_that_widens(K, M, ngs):
+    """A GCN layer whose output is wider than its input aggregates first; with GNN_FLAG_FUSION the Update is
+    fused into that aggregation (wave-tile form with the edge weights beside the indices, no own-row term)
+    where the shape is covered.  Oracle values with the Eq. 2 weights; then integer-valued data and weights,
+    for which every sum is exact: bit-equal to the oracle and from run to run."""
+    g = config_graph(4, shrink=16)
+    ew = oracle.gcn_norm(g.rowptr, g.colidx)
+    G = DeviceGraph(g.rowptr, g.colidx, ew)
+    X = features(g.n, K, seed=K + M)
+    W = glorot(K, M, seed=M)
+    b = features(1, M, seed=ngs)[0] * 0.1
+    ref, scale = oracle.gcn_layer(g.rowptr, g.colidx, ew, X, W, b, True, want_abs=True)
+    ws = gnn.alloc_workspace(G.n, G.nnz, max(K, M), ngs)
+    out = torch.full((g.n, M), float("nan"), device="cuda")
+    gnn.gnn_layer_forward(gnn.GNN_GCN, G.n, G.nnz, G.rowptr, G.colidx, G.ew, 0.0, dev(X), K, dev(W), dev(b), M, True, out,
+                          ngs, 0, 0, gnn.GNN_FLAG_FUSION, ws)
+    torch.cuda.synchronize()
+    gnn.gnn_workspace_status(ws)
+    name = gnn.gnn_bench_last_aggregation()
+    covered = M <= 64
+    assert name.startswith("k_gin_layer_fused_w") == covered, name
+    assert_parity(out.cpu().numpy(), ref, scale, f"fused gcn layer {K}->{M} ngs {ngs}")
+
+    rng = np.random.default_rng(K * M + ngs)
+    Xi = rng.integers(-3, 4, size=(g.n, K)).astype(np.float32)
+    Wi = rng.integers(-2, 3, size=(K, M)).astype(np.float32)
+    bi = rng.integers(-4, 5, size=M).astype(np.float32)
+    ewi = rng.integers(1, 3, size=g.nnz).astype(np.float32)
+    refi = oracle.gcn_layer(g.rowptr, g.colidx, ewi, Xi, Wi, bi, True)
+    Gi = DeviceGraph(g.rowptr, g.colidx, ewi)
+    outs = []
+    for _ in range(2):
+        out = torch.full((g.n, M), float("nan"), device="cuda")
+        gnn.gnn_layer_forward(gnn.GNN_GCN, Gi.n, Gi.nnz, Gi.rowptr, Gi.colidx, Gi.ew, 0.0, dev(Xi), K, dev(Wi), dev(bi), M, True,
+                              out, ngs, 0, 0, gnn.GNN_FLAG_FUSION, ws)
+        torch.cuda.synchronize()
+        gnn.gnn_workspace_status(ws)
+        outs.append(out.cpu().numpy())
+    assert np.array_equal(outs[0], refi.astype(np.float32)), np.abs(outs[0] - refi).max()
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+
+
 def test_fused_layer_takes_the_block_tile_form_where_the_wave_tile_form_does_not_apply():
     # rows of 96 floats, and groups of more entries than a team keeps in registers
     g = config_graph(3, shrink=8)
