@@ -251,6 +251,19 @@ int gnn_aggregate_reduce(int op, int32_t n, int64_t nnz, const int32_t *rowptr, 
                          int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
                          void *stream);
 
+/* Aggregation with a feature vector on every stored entry (Sec. 3.1: the second class of aggregation applies
+ * edge features to each neighbor; the paper does not fix the combination, the reading here is the
+ * elementwise product): out[i,:] = sum over the stored entries e = (i, j) of row i of E[e,:] * X[j,:].
+ * E: DEVICE float[nnz, dim], one row per stored entry in CSR order, read once.  No scalar weights, no self
+ * term; a row without entries gives 0.  Scalar edge weights go through the ew argument of
+ * gnn_aggregate_gcn instead.  Uses the ordered flush, so the workspace must be sized with max_dim >= dim
+ * (GNN_EWORKSPACE otherwise) and the flags GNN_FLAG_NO_BLOCK_OPT, _ATOMIC_FLUSH, _FUSION are refused
+ * (GNN_EINVAL).  Everything else as for gnn_aggregate_gcn. */
+int gnn_aggregate_edge(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *E,
+                       const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw,
+                       int32_t waves_per_block, uint32_t flags, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
 /* Update phase alone (Sec. 2.1, w.a + b): out[n,M] = act(A[n,K] W[K,M] + b), fp32 MFMA.
  * b NULL or float[M]; relu 0/1.  DEVICE pointers. */
 int gnn_update_gemm(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b,

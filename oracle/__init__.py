@@ -68,6 +68,19 @@ def aggregate_gcn(rowptr, colidx, ew, X, want_abs: bool = False):
     return (out, ab) if want_abs else out
 
 
+def aggregate_edge_vec(rowptr, colidx, E, X, want_abs: bool = False):
+    """Aggregation with a feature vector per stored entry (Sec. 3.1): out_i = sum_e E[e,:] * X[colidx[e],:]
+    elementwise, E float32 [nnz, dim] in CSR order."""
+    rowptr, colidx, X, E = _i32(rowptr), _i32(colidx), _f32(X), _f32(E)
+    n, dim = rowptr.size - 1, X.shape[1]
+    assert E.shape == (colidx.size, dim)
+    out = np.empty((n, dim), dtype=np.float32)
+    ab = np.empty((n, dim), dtype=np.float64) if want_abs else None
+    _L().orc_aggregate_edge_vec(ctypes.c_int32(n), _p(rowptr), _p(colidx), _p(E), _p(X), ctypes.c_int32(dim),
+                                _p(out), _p(ab))
+    return (out, ab) if want_abs else out
+
+
 def aggregate_gin(rowptr, colidx, eps: float, X, want_abs: bool = False):
     """Eq. 3 aggregation: out_i = (1+eps) x_i + sum_{j in N(i)} x_j."""
     rowptr, colidx, X = _i32(rowptr), _i32(colidx), _f32(X)

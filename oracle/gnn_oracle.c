@@ -16,6 +16,8 @@
  *                         star_graph_closed_form, linearity_and_eps_term, empty_graph_and_isolated_nodes,
  *                         oracle_against_a_library_sparse_product; abs_out: layers.py:
  *                         aggregation_error_scales_are_the_sums_of_absolute_terms
+ *   orc_aggregate_edge_vec edge_vec.py: matches_the_dense_tensor_expression, constant_vectors_reduce_to_the_weighted_sum,
+ *                         one_hot_vectors_select_single_dimensions, hand_worked_triangle, renumbering_invariance
  *   orc_aggregate_f64     layers.py: gcn_layer_error_scale_equals_the_dense_expression
  *   orc_aggregate_gin     aggregate.py: gin_matches_dense_product, all_ones..., linearity_and_eps_term,
  *                         empty_graph_and_isolated_nodes; abs_out as above
@@ -65,6 +67,27 @@ void orc_aggregate_gcn(int32_t n, const int32_t *rowptr, const int32_t *colidx, 
             for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
                 double w = ew ? (double)ew[e] : 1.0;
                 double t = w * (double)X[(size_t)colidx[e] * dim + k];
+                acc += t;
+                aacc += fabs(t);
+            }
+            out[(size_t)i * dim + k] = (float)acc;
+            if (abs_out) abs_out[(size_t)i * dim + k] = aacc;
+        }
+    }
+}
+
+/* Aggregation with a feature vector on every stored entry (Sec. 3.1, the second class of aggregation:
+ * edge features applied to each neighbor): out[i,k] = sum over stored entries e of row i of
+ * E[e,k] * X[colidx[e],k].  E holds one row of dim floats per stored entry, in CSR order.  A vector whose
+ * dim entries all equal a scalar w[e] gives orc_aggregate_gcn with the weights w. */
+void orc_aggregate_edge_vec(int32_t n, const int32_t *rowptr, const int32_t *colidx, const float *E,
+                            const float *X, int32_t dim, float *out, double *abs_out)
+{
+    for (int32_t i = 0; i < n; ++i) {
+        for (int32_t k = 0; k < dim; ++k) {
+            double acc = 0.0, aacc = 0.0;
+            for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+                double t = (double)E[(size_t)e * dim + k] * (double)X[(size_t)colidx[e] * dim + k];
                 acc += t;
                 aacc += fabs(t);
             }

@@ -11,7 +11,7 @@ __all__ = [
     "GnnError", "lib_path", "load", "exported_symbols",
     "GNN_GCN", "GNN_GIN", "GNN_FLAG_REUSE_PARTITION", "GNN_FLAG_NO_BLOCK_OPT", "GNN_FLAG_XCD_RUNS", "GNN_FLAG_NO_PIPELINE",
     "GNN_FLAG_PIPELINE", "GNN_FLAG_DETERMINISTIC", "GNN_FLAG_FUSION", "GNN_FLAG_ATOMIC_FLUSH", "GNN_FLAG_GCN_NARROW_FIRST", "GNN_FLAG_GCN_UPDATE_FIRST", "GNN_FLAG_NO_FUSION", "GNN_REDUCE_SUM", "GNN_REDUCE_MAX", "GNN_REDUCE_MIN",
-    "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall", "AggregateCall",
+    "GNN_REDUCE_MEAN", "gnn_aggregate_reduce", "gnn_aggregate_edge", "gnn_model_workspace_bytes", "gnn_model_forward", "ModelCall", "AggregateCall",
     "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
     "gnn_bench_stream_read", "gnn_bench_gather_rows", "gnn_csr_transpose_device", "gnn_bench_last_aggregation",
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
@@ -40,7 +40,7 @@ _SYMBOLS = [
     "gnn_reorder", "gnn_aes", "gnn_gcn_norm", "gnn_apply_perm_csr", "gnn_decide", "gnn_paper_model",
     "gnn_workspace_bytes", "gnn_partition_build", "gnn_workspace_status", "gnn_partition_export",
     "gnn_block_layout_export", "gnn_validate_csr_device", "gnn_aggregate_gcn", "gnn_aggregate_gin", "gnn_aggregate_gin_static",
-    "gnn_aggregate_reduce", "gnn_model_workspace_bytes", "gnn_model_forward",
+    "gnn_aggregate_reduce", "gnn_aggregate_edge", "gnn_model_workspace_bytes", "gnn_model_forward",
     "gnn_update_gemm", "gnn_layer_forward", "gnn_layer_forward_timed", "gnn_permute_rows", "gnn_strerror",
     "gnn_last_hip_error", "gnn_version", "gnn_csr_transpose", "gnn_backward_workspace_bytes", "gnn_layer_backward",
     "gnn_reorder_device", "gnn_apply_perm_csr_device", "gnn_gcn_norm_device", "gnn_aes_device",
@@ -341,6 +341,16 @@ def gnn_aggregate_reduce(op, n, nnz, rowptr, colidx, X, out, dim, ngs=0, dw=0, w
                                      _dev(out, "float32", "out"), _i32(dim), _i32(ngs), _i32(dw),
                                      _i32(waves_per_block), _u32(flags), wp, wb, _stream(stream))
     _check(rc, "gnn_aggregate_reduce")
+
+
+def gnn_aggregate_edge(n, nnz, rowptr, colidx, E, X, out, dim, ngs=0, dw=0, waves_per_block=0, flags=0, workspace=None,
+                       stream=None):
+    wp, wb = _ws(workspace)
+    rc = load().gnn_aggregate_edge(_i32(n), _i64(nnz), _dev(rowptr, "int32", "rowptr"), _dev(colidx, "int32", "colidx"),
+                                   _dev(E, "float32", "E"), _dev(X, "float32", "X"), _dev(out, "float32", "out"),
+                                   _i32(dim), _i32(ngs), _i32(dw), _i32(waves_per_block), _u32(flags), wp, wb,
+                                   _stream(stream))
+    _check(rc, "gnn_aggregate_edge")
 
 
 def gnn_update_gemm(n, K, M, A, W, b, relu, out, stream=None):

@@ -15,6 +15,7 @@ struct AggParams {
     const int *ngptr;
     const int *colidx;
     const float *ew;
+    const float *evec;  // per-entry feature vectors [nnz, dim] multiplied into the neighbour rows elementwise, or null
     const float *X;
     float *out;
     float *part_rows;    // ordered flush: float[2 * tiles * dim] partial rows of spanning nodes; else null

@@ -102,10 +102,13 @@ __global__ __launch_bounds__(256) void k_agg_epilogue_spanning(AggParams p)
 // for the ITER chunks that start at chunk c0, acc[c][:] = reduce over the group's staged entries of
 // w * X[col, chunk c].  U neighbour rows are in flight per lane.  GIN's own row (SELF, first group of
 // the node) is one more term of the first batch, so no load waits for another.
-template <int VEC, int ITER, int U, bool WEIGHTED, bool SELF, int OP, bool FULL>
+// EVEC: every stored entry carries a vector of dim floats (Sec. 3.1, aggregation with edge features); the
+// neighbour row is multiplied by it elementwise.  The vectors of a group are consecutive rows of E starting
+// at erow0, read once, in order.
+template <int VEC, int ITER, int U, bool WEIGHTED, bool SELF, int OP, bool FULL, bool EVEC = false>
 __device__ __forceinline__ void gather_rows(float (&acc)[ITER][VEC], const float *__restrict__ X, const int *lc,
                                             const float *lw, int len, int node, bool self_term, float self_scale,
-                                            int dim, int dwl, int tlane, int c0)
+                                            int dim, int dwl, int tlane, int c0, const float *__restrict__ erow0 = nullptr)
 {
     bool dok[ITER];
     const float *xb = X + (size_t)(c0 * dwl + tlane) * VEC;
@@ -134,25 +137,34 @@ __device__ __forceinline__ void gather_rows(float (&acc)[ITER][VEC], const float
             if (SELF) w[u] = k < 0 ? self_scale : 1.0f;
         }
         float v[U][ITER][VEC];
+        float ev[EVEC ? U : 1][ITER][VEC];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (col[u] >= 0) {
                 // 32 x 32 -> 64-bit product: one multiply-add per address
                 const float *row = xb + (size_t)(unsigned)col[u] * (unsigned)dim;
+                const float *er = EVEC ? erow0 + (size_t)(unsigned)(base + u) * (unsigned)dim + (size_t)(c0 * dwl + tlane) * VEC : nullptr;
 #pragma unroll
                 for (int c = 0; c < ITER; ++c) {
                     if (dok[c]) {
                         load_vec<VEC>(v[u][c], row + (size_t)c * dwl * VEC);
+                        if (EVEC) load_vec<VEC>(ev[u][c], er + (size_t)c * dwl * VEC);
                     } else {
 #pragma unroll
-                        for (int j = 0; j < VEC; ++j) v[u][c][j] = op_identity<OP>();
+                        for (int j = 0; j < VEC; ++j) {
+                            v[u][c][j] = op_identity<OP>();
+                            if (EVEC) ev[u][c][j] = 0.0f;
+                        }
                     }
                 }
             } else {
 #pragma unroll
                 for (int c = 0; c < ITER; ++c)
 #pragma unroll
-                    for (int j = 0; j < VEC; ++j) v[u][c][j] = op_identity<OP>();
+                    for (int j = 0; j < VEC; ++j) {
+                        v[u][c][j] = op_identity<OP>();
+                        if (EVEC) ev[u][c][j] = 0.0f;
+                    }
             }
         }
 #pragma unroll
@@ -161,7 +173,8 @@ __device__ __forceinline__ void gather_rows(float (&acc)[ITER][VEC], const float
             for (int c = 0; c < ITER; ++c)
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
-                    if (WEIGHTED || SELF) acc[c][j] = fmaf(w[u], v[u][c][j], acc[c][j]);
+                    if (EVEC) acc[c][j] = fmaf(ev[u][c][j], v[u][c][j], acc[c][j]);
+                    else if (WEIGHTED || SELF) acc[c][j] = fmaf(w[u], v[u][c][j], acc[c][j]);
                     else acc[c][j] = op_combine<OP>(acc[c][j], v[u][c][j]);
                 }
     }
@@ -214,7 +227,7 @@ __device__ __forceinline__ void store_row(const AggParams &p, const float (&acc)
 // pass with every lane of a team in range (dim == ITER * dw * VEC), so no lane needs a bounds check.
 // The sums over 16-byte loads of such rows get (DL, FULL = true); everything else (narrow loads, rows
 // that leave lanes idle or need several passes, max / min) runs the (DL = -1, FULL = false) form.
-template <int VEC, int ITER, int U, int DL, bool WEIGHTED, bool SELF, int OP, bool FULL>
+template <int VEC, int ITER, int U, int DL, bool WEIGHTED, bool SELF, int OP, bool FULL, bool EVEC = false>
 __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -329,8 +342,9 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
 
     for (int c0 = 0; c0 < (FULL ? 1 : p.iter_total); c0 += ITER) {
         float acc[ITER][VEC];
-        gather_rows<VEC, ITER, U, WEIGHTED, SELF, OP, FULL>(acc, p.X, lc, lw, len, e.node, first && len > 0, p.self_scale, dim, dwl,
-                                                            tlane, c0);
+        gather_rows<VEC, ITER, U, WEIGHTED, SELF, OP, FULL, EVEC>(acc, p.X, lc, lw, len, e.node, first && len > 0, p.self_scale,
+                                                                  dim, dwl, tlane, c0,
+                                                                  EVEC ? p.evec + (size_t)(unsigned)e.start * (unsigned)dim : nullptr);
 
         // Algorithm 1 inside the wave: a team opens a segment when its target node differs from the team's
         // before it; the segment's first team collects the segment's sum
@@ -547,7 +561,11 @@ template <int VEC, int ITER, int U, int DL, bool FULL>
 static void launch_one(int op, bool weighted, bool self, dim3 grid, dim3 block, size_t lds, hipStream_t s,
                        const AggParams &p)
 {
-    if (op == kOpMax) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, -1, false, false, kOpMax, false>), grid, block, lds, s, p);
+    if (p.evec) {
+        // half the rows in flight: every neighbour row comes with a row of edge features
+        constexpr int UE = U >= 2 ? U / 2 : 1;
+        hipLaunchKernelGGL((k_aggregate<VEC, ITER, UE, -1, false, false, kOpSum, false, true>), grid, block, lds, s, p);
+    } else if (op == kOpMax) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, -1, false, false, kOpMax, false>), grid, block, lds, s, p);
     else if (op == kOpMin) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, -1, false, false, kOpMin, false>), grid, block, lds, s, p);
     else if (self) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, DL, false, true, kOpSum, FULL>), grid, block, lds, s, p);
     else if (weighted) hipLaunchKernelGGL((k_aggregate<VEC, ITER, U, DL, true, false, kOpSum, FULL>), grid, block, lds, s, p);
@@ -562,7 +580,7 @@ static void launch_main(int op, bool weighted, bool self, dim3 grid, dim3 block,
                         const AggParams &p)
 {
     if constexpr (VEC == 4) {
-        if (p.full_rows && op == kOpSum) {
+        if (p.full_rows && op == kOpSum && !p.evec) {
             switch (p.dwl_log2) {
                 case 0: launch_one<VEC, ITER, U, 0, true>(op, weighted, self, grid, block, lds, s, p); break;
                 case 1: launch_one<VEC, ITER, U, 1, true>(op, weighted, self, grid, block, lds, s, p); break;
@@ -624,9 +642,13 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
                           const int32_t *colidx, const float *ew, const float *X, float *out, int32_t dim, int32_t ngs,
                           int32_t dw, int32_t wpb, uint32_t flags, const float *bias, int relu, void *workspace,
                           size_t workspace_bytes, size_t ws_reserved, hipStream_t s, hipEvent_t ev_start,
-                          hipEvent_t ev_stop, FuseSpec *fuse)
+                          hipEvent_t ev_stop, FuseSpec *fuse, const float *evec)
 {
     const bool plain_sum = op == kOpSum && !mean;
+    // per-entry feature vectors: plain sum, no scalar weights, no self term, ordered flush only
+    if (evec && (!plain_sum || ew || self || fuse ||
+                 (flags & (GNN_FLAG_NO_BLOCK_OPT | GNN_FLAG_ATOMIC_FLUSH | GNN_FLAG_FUSION))))
+        return GNN_EINVAL;
     if (op != kOpSum && op != kOpMax && op != kOpMin) return GNN_EINVAL;
     if (!plain_sum && (mean && op != kOpSum)) return GNN_EINVAL;
     if (!plain_sum && (ew || self || fuse)) return GNN_EINVAL;
@@ -665,6 +687,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     p.ngptr = (const int *)(ws + L.ngptr);
     p.colidx = colidx;
     p.ew = ew;
+    p.evec = evec;
     p.X = X;
     p.out = out;
     p.part_rows = nullptr;
@@ -765,7 +788,7 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
     }
 
     // the workspace-size functions allow deterministic scratch for blocks of kPartMinTile groups
-    if ((det || !plain_sum) && auto_wpb)
+    if ((det || !plain_sum || evec) && auto_wpb)
         while (wpb * (64 >> dwl_log2) < kPartMinTile && wpb < kMaxWavesPerBlock) wpb *= 2;
     const int T = wpb * (64 >> dwl_log2);
     p.T = T;
@@ -785,9 +808,9 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
         off = align_up(off);
         if (off + part_rows_bytes(ng_cap, T, dim) <= workspace_bytes) part_rows = (float *)(ws + off);
     }
-    if ((det || !plain_sum) && !part_rows) return GNN_EWORKSPACE;
+    if ((det || !plain_sum || evec) && !part_rows) return GNN_EWORKSPACE;
 
-    const bool ordered = det || (part_rows != nullptr && !atomic_flush);
+    const bool ordered = det || evec != nullptr || (part_rows != nullptr && !atomic_flush);
 
     int64_t grid = tiles_upper;
     if (p.xcd_remap) grid = (tiles_upper + kNumXcd * kXcdRun - 1) / (kNumXcd * kXcdRun) * (kNumXcd * kXcdRun);
@@ -813,6 +836,10 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
         else if (vec == 2) launch_vec<2>(op, iter, weighted, self, g, b, lds, s, p);
         else launch_vec<1>(op, iter, weighted, self, g, b, lds, s, p);
     }
+    if (evec) {
+        const int u = unroll_of(vec, iter);
+        note_launch("k_aggregate(edge vectors)", vec, iter, u >= 2 ? u / 2 : 1, -1, false, false, op, T, ngs, wpb, ordered, p.xcd_remap != 0);
+    } else
     note_launch("k_aggregate", vec, iter, unroll_of(vec, iter), (vec == 4 && op == kOpSum && p.full_rows) ? dwl_log2 : -1,
                 weighted && op == kOpSum, self && op == kOpSum, op, T, ngs,
                 wpb, ordered, p.xcd_remap != 0);
@@ -919,6 +946,18 @@ int gnn_aggregate_reduce(int op, int32_t n, int64_t nnz, const int32_t *rowptr, 
     return aggregate_reduce_impl(kop, mean, false, 0.0f, n, nnz, rowptr, colidx, nullptr, X, out, dim, ngs, dw,
                                  waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, 0, (hipStream_t)stream,
                                  nullptr, nullptr, nullptr);
+}
+
+int gnn_aggregate_edge(int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *E,
+                       const float *X, float *out, int32_t dim, int32_t ngs, int32_t dw, int32_t waves_per_block,
+                       uint32_t flags, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (nnz > 0 && !E) return GNN_EINVAL;
+    if (nnz == 0) E = nullptr;
+    // (a graph without entries: every row is 0, which the plain sum writes)
+    return aggregate_reduce_impl(kOpSum, false, false, 0.0f, n, nnz, rowptr, colidx, nullptr, X, out, dim, ngs, dw,
+                                 waves_per_block, flags, nullptr, 0, workspace, workspace_bytes, 0, (hipStream_t)stream,
+                                 nullptr, nullptr, nullptr, E);
 }
 
 }  // extern "C"

@@ -20,11 +20,12 @@ int partition_build_impl(int32_t n, int64_t nnz, const int32_t *rowptr, int32_t 
 // (may be null) are recorded around the main kernel.  fuse (may be null): see FuseSpec.
 // op: kOpSum / kOpMax / kOpMin; mean: divide every finished row by its length (op must be kOpSum).
 // Anything but the plain sum takes no weights, no self term, and needs the ordered flush.
+// evec (may be null): per-entry feature vectors [nnz, dim], multiplied into the neighbour rows elementwise.
 int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr,
                           const int32_t *colidx, const float *ew, const float *X, float *out, int32_t dim, int32_t ngs,
                           int32_t dw, int32_t wpb, uint32_t flags, const float *bias, int relu, void *workspace,
                           size_t workspace_bytes, size_t ws_reserved, hipStream_t s, hipEvent_t ev_start,
-                          hipEvent_t ev_stop, FuseSpec *fuse);
+                          hipEvent_t ev_stop, FuseSpec *fuse, const float *evec = nullptr);
 
 inline int aggregate_impl(bool self, float self_scale, int32_t n, int64_t nnz, const int32_t *rowptr,
                           const int32_t *colidx, const float *ew, const float *X, float *out, int32_t dim, int32_t ngs,
