@@ -769,11 +769,10 @@ int aggregate_reduce_impl(int op, bool mean, bool self, float self_scale, int32_
             pf.part_rows = (float *)(ws + off);
             if (ev_start) GNN_HIP_TRY(hipEventRecord(ev_start, s));
             const int rc = try_gin_layer_fused(pf, vec, wpb_f, fuse->W, fuse->b, fuse->out, fuse->M, fuse->relu,
-                                                (ng_cap + pf.T - 1) / pf.T, s);
+                                                (ng_cap + pf.T - 1) / pf.T, s, &wpb_f);
             if (rc < 0) return rc;
             if (rc == GNN_OK) {
                 const int it_f = p.iter_total < 4 ? p.iter_total : 4;
-                if (wave_tiles) wpb_f = pf.extra_blocks;  // (the wave-tile form reports its waves per block there)
                 note_launch(wave_tiles ? "k_gin_layer_fused_w" : "k_gin_layer_fused", vec, it_f, unroll_of(vec, it_f),
                             wave_tiles ? dwl_log2 : -1, weighted, self, op, pf.T, ngs, wpb_f, true, p.xcd_remap != 0);
                 if (ev_stop) GNN_HIP_TRY(hipEventRecord(ev_stop, s));

@@ -851,7 +851,7 @@ bool gin_layer_fused_wave_tiles(const AggParams &p, int vec, int M)
 }
 
 static int launch_gin_layer_fused_w(AggParams &p, const float *W, const float *b, float *out, int M, int relu,
-                                    int64_t ng_cap, hipStream_t s)
+                                    int64_t ng_cap, hipStream_t s, int *waves_used)
 {
     const int dwl = 1 << p.dwl_log2;
     const int K = p.dim;
@@ -883,23 +883,20 @@ static int launch_gin_layer_fused_w(AggParams &p, const float *W, const float *b
     fp.a_rows = 16;
     void *args[] = {(void *)&fp};
     GNN_HIP_TRY(hipLaunchKernel(fn, dim3((unsigned)(grid + extra)), dim3((unsigned)(nw * 64)), args, lds, s));
-    return nw;
+    if (waves_used) *waves_used = nw;
+    return GNN_OK;
 }
 
 // Tries the fused GIN layer.  Returns GNN_OK after enqueueing it, 1 if the shape is outside what it
 // covers (the caller then runs aggregation and GEMM separately), < 0 on error.  p.part_rows must
 // point to room for 2 * tiles rows of max(K, M) floats.
 int try_gin_layer_fused(AggParams &p, int vec, int wpb, const float *W, const float *b, float *out, int M, int relu,
-                         int64_t tiles_upper, hipStream_t s)
+                         int64_t tiles_upper, hipStream_t s, int *waves_used)
 {
+    if (waves_used) *waves_used = wpb;
     if (p.T == kFusedWaveTile && gin_layer_fused_wave_tiles(p, vec, M)) {
         // (the caller sized the partial rows for tiles of 16 groups)
-        const int rc = launch_gin_layer_fused_w(p, W, b, out, M, relu, tiles_upper * kFusedWaveTile, s);
-        if (rc > 1) {  // launched, with rc waves per block
-            p.extra_blocks = rc;
-            return GNN_OK;
-        }
-        return rc;
+        return launch_gin_layer_fused_w(p, W, b, out, M, relu, tiles_upper * kFusedWaveTile, s, waves_used);
     }
     if (p.ew) return 1;  // (the block-tile form has no edge weights)
     const int K = p.dim;

@@ -42,8 +42,9 @@ void launch_agg_epilogue_spanning(const AggParams &p, hipStream_t s);
 // gnn_gin_fused.hip: GIN aggregation with the Update fused in, on the general kernel with the ordered
 // flush; p.part_rows must have room for rows of max(p.dim, M) floats.  Returns GNN_OK when the fused
 // kernel was launched, 1 when the shape does not qualify (nothing launched), < 0 on error.
+// waves_used (may be null) receives the waves per block of the kernel that was launched.
 int try_gin_layer_fused(AggParams &p, int vec, int wpb, const float *W, const float *b, float *out, int M, int relu,
-                        int64_t tiles_upper, hipStream_t s);
+                        int64_t tiles_upper, hipStream_t s, int *waves_used);
 // true if the wave-tile form of the fused layer covers the shape; the caller then sets p.T = 16 and sizes the
 // partial rows for tiles of 16 groups before it calls try_gin_layer_fused
 bool gin_layer_fused_wave_tiles(const AggParams &p, int vec, int M);
