@@ -380,6 +380,67 @@ def test_fused_gcn_layer_that_widens(K, M, ngs):
     assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
 
 
+def _random_graph(rng):
+    """Degrees from one of several shapes (regular, short rows, a few hubs, many empty rows); duplicate and
+    self entries allowed."""
+    n = int(rng.choice([1, 17, 300, 5000, 40000]))
+    kind = int(rng.integers(0, 4))
+    if kind == 0:
+        deg = np.full(n, int(rng.integers(1, 9)))
+    elif kind == 1:
+        deg = rng.integers(0, 11, size=n)
+    elif kind == 2:
+        deg = rng.integers(0, 4, size=n)
+        deg[rng.integers(0, n, size=max(1, n // 200))] = rng.integers(200, 3000)
+    else:
+        deg = np.where(rng.random(n) < 0.7, 0, rng.integers(1, 40, size=n))
+    rp = np.zeros(n + 1, dtype=np.int32)
+    rp[1:] = np.cumsum(deg)
+    ci = rng.integers(0, n, size=int(rp[-1])).astype(np.int32)
+    return rp, ci
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_fused_layers_on_random_graphs_and_shapes(seed):
+    """Random graphs, widths, group sizes, team widths, bias / activation, GIN and widening GCN layers with
+    GNN_FLAG_FUSION: whichever form of the fused layer the library picks (or none, where no form covers the
+    shape) must match the oracle, and a second run must repeat the first bit for bit."""
+    rng = np.random.default_rng(7000 + seed)
+    rp, ci = _random_graph(rng)
+    n, nnz = rp.size - 1, ci.size
+    K = int(rng.choice([16, 32, 64, 64, 24, 128]))
+    M = int(rng.choice([1, 3, 16, 22, 48, 64, 64, 70]))
+    ngs = int(rng.choice([0, 1, 2, 5, 8, 16, 32, 64]))
+    dw = int(rng.choice([0, 0, 4, 8, 16]))
+    gcn = bool(rng.integers(0, 2)) and M > K
+    relu = bool(rng.integers(0, 2))
+    X = features(n, K, seed=seed)
+    W = glorot(K, M, seed=seed + 1)
+    b = features(1, M, seed=seed + 2)[0] if rng.integers(0, 2) else None
+    what = f"seed {seed}: n {n} nnz {nnz} {'gcn' if gcn else 'gin'} {K}->{M} ngs {ngs} dw {dw} relu {relu} bias {b is not None}"
+    print(what, flush=True)
+    if gcn:
+        ew = rng.standard_normal(nnz).astype(np.float32)
+        ref, scale = oracle.gcn_layer(rp, ci, ew, X, W, b, relu, want_abs=True)
+        G, kind, eps = DeviceGraph(rp, ci, ew), gnn.GNN_GCN, 0.0
+    else:
+        eps = float(rng.choice([0.0, 0.5, -1.0]))
+        ref, scale = oracle.gin_layer(rp, ci, eps, X, W, b, relu, want_abs=True)
+        G, kind = DeviceGraph(rp, ci), gnn.GNN_GIN
+    ws = gnn.alloc_workspace(n, nnz, max(K, M), ngs)
+    outs = []
+    for _ in range(2):
+        out = torch.full((n, M), float("nan"), device="cuda")
+        gnn.gnn_layer_forward(kind, n, nnz, G.rowptr, G.colidx, G.ew if gcn else None, eps, dev(X), K, dev(W), dev(b), M, relu,
+                              out, ngs, dw, 0, gnn.GNN_FLAG_FUSION, ws)
+        torch.cuda.synchronize()
+        gnn.gnn_workspace_status(ws)
+        outs.append(out.cpu().numpy())
+    print("   ", gnn.gnn_bench_last_aggregation(), flush=True)
+    assert_parity(outs[0], ref, scale, what)
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32)), what
+
+
 def test_fused_layer_takes_the_block_tile_form_where_the_wave_tile_form_does_not_apply():
     # rows of 96 floats, and groups of more entries than a team keeps in registers
     g = config_graph(3, shrink=8)
