@@ -86,6 +86,8 @@ def main():
                          "configuration 5 'natural' (R-MAT ids not scrambled)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step in a HIP graph and time replays (launch-bound small configurations)")
+    ap.add_argument("--edge-vectors", action="store_true",
+                    help="also time gnn_aggregate_edge (a feature vector per stored entry, Sec. 3.1) at the headline width")
     ap.add_argument("--train", action="store_true",
                     help="also time a training step (forward + gnn_layer_backward of every layer, no optimizer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -226,6 +228,30 @@ def main():
     hb.record()
     torch.cuda.synchronize()
     head_call_ms = ha.elapsed_time(hb) / args.steps
+
+    # ---- optional: aggregation with a feature vector on every stored entry, at the same width
+    edge_vec = None
+    if args.edge_vectors:
+        Ev = torch.randn(nnz, head_dim, device="cuda")
+        oute = torch.empty(n, head_dim, device="cuda")
+        wse = gnn.alloc_workspace(n, nnz, head_dim, ngs)
+        gnn.gnn_partition_build(n, nnz, rp, ngs, wse)
+        for _ in range(args.warmup):
+            gnn.gnn_aggregate_edge(n, nnz, rp, ci, Ev, Xh, oute, head_dim, ngs, args.dw, args.wpb, REUSE, wse)
+        torch.cuda.synchronize()
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ea.record()
+        for _ in range(args.steps):
+            gnn.gnn_aggregate_edge(n, nnz, rp, ci, Ev, Xh, oute, head_dim, ngs, args.dw, args.wpb, REUSE, wse)
+        eb.record()
+        torch.cuda.synchronize()
+        gnn.gnn_workspace_status(wse)
+        ev_ms = ea.elapsed_time(eb) / args.steps
+        ev_bytes = nnz * head_dim * 4 + 2 * n * head_dim * 4 + nnz * 4 + 4 * n  # E once, X once, out once, indices
+        edge_vec = {"dim": head_dim, "call_ms": ev_ms, "edge_vector_bytes": nnz * head_dim * 4,
+                    "compulsory_bytes": ev_bytes, "compulsory_GBps": ev_bytes / (ev_ms * 1e-3) / 1e9,
+                    "kernel": gnn.gnn_bench_last_aggregation()}
+        del Ev, oute, wse
 
     # ---- the step: the configuration's model forward (configuration 1: the single aggregation)
     nlay = max(layers, 1)
@@ -519,6 +545,7 @@ def main():
         "headline_aggregation": {"dim": head_dim, "call_ms": head_call_ms,
                                  "edges_dim_per_s": float(nnz) * head_dim / (head_call_ms * 1e-3),
                                  "algorithmic_GBps": algorithmic_bytes(head_dim) / (head_call_ms * 1e-3) / 1e9},
+        "edge_vector_aggregation": edge_vec,
         "prep": prep,
         "dims": dims,
         "step_api": "gnn_model_forward" if layers else "gnn_aggregate_gcn",
