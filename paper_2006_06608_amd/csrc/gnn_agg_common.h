@@ -134,6 +134,23 @@ __device__ __forceinline__ void store_vec_stream(float *p, const float (&r)[VEC]
 #endif
 }
 
+// A row that is read exactly once (a node's own row, the rows without entries): streaming load.
+template <int VEC>
+__device__ __forceinline__ void load_vec_stream(float (&r)[VEC], const float *p)
+{
+    typedef float v4 __attribute__((ext_vector_type(4)));
+    typedef float v2 __attribute__((ext_vector_type(2)));
+    if constexpr (VEC == 4) {
+        const v4 t = __builtin_nontemporal_load(reinterpret_cast<const v4 *>(p));
+        r[0] = t[0]; r[1] = t[1]; r[2] = t[2]; r[3] = t[3];
+    } else if constexpr (VEC == 2) {
+        const v2 t = __builtin_nontemporal_load(reinterpret_cast<const v2 *>(p));
+        r[0] = t[0]; r[1] = t[1];
+    } else {
+        r[0] = __builtin_nontemporal_load(p);
+    }
+}
+
 // Column indices, edge weights and group tuples are read exactly once.
 template <typename T>
 __device__ __forceinline__ T load_stream(const T *p)
@@ -248,7 +265,8 @@ __device__ __forceinline__ void write_empty_rows(const AggParams &p, int64_t fir
                 for (int q = 0; q < 4; ++q) {
 #pragma unroll
                     for (int j = 0; j < VEC; ++j) r[q][j] = 0.0f;
-                    if (SELF && ok[q]) load_vec<VEC>(r[q], p.X + (size_t)node[q] * dim + d);
+                    // (read once: a streaming load keeps these rows from displacing the hubs' rows in L2)
+                    if (SELF && ok[q]) load_vec_stream<VEC>(r[q], p.X + (size_t)node[q] * dim + d);
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {

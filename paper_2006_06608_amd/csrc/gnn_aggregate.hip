@@ -148,7 +148,7 @@ __device__ __forceinline__ void gather_rows(float (&acc)[ITER][VEC], const float
                 for (int c = 0; c < ITER; ++c) {
                     if (dok[c]) {
                         load_vec<VEC>(v[u][c], row + (size_t)c * dwl * VEC);
-                        if (EVEC) load_vec<VEC>(ev[u][c], er + (size_t)c * dwl * VEC);
+                        if (EVEC) load_vec_stream<VEC>(ev[u][c], er + (size_t)c * dwl * VEC);
                     } else {
 #pragma unroll
                         for (int j = 0; j < VEC; ++j) {
