@@ -269,11 +269,12 @@ int gnn_aggregate_edge(int32_t n, int64_t nnz, const int32_t *rowptr, const int3
 int gnn_update_gemm(int32_t n, int32_t K, int32_t M, const float *A, const float *W, const float *b,
                     int relu, float *out, void *stream);
 
-/* One GNN layer (Eq. 1).  kind GNN_GCN: out = act(A_hat (X W) + b);  GNN_GIN:
- * out = act(((1+eps) X + sum_N X) W + b).  X float[n*in_dim], W float[in_dim*out_dim] row-major,
- * b NULL or float[out_dim], out float[n*out_dim].  The intermediate lives in the workspace
- * (size it with max_dim = out_dim for GCN, in_dim for GIN).  ew is used by GNN_GCN only, eps by
- * GNN_GIN only. */
+/* One GNN layer (Eq. 1).  kind GNN_GCN: out = act(A_hat (X W) + b), computed as Update then
+ * Aggregation when out_dim <= in_dim and as act((A_hat X) W + b), Aggregation then Update, when the layer
+ * widens (Sec. 3.1: the aggregation runs at the smaller width; GNN_FLAG_GCN_UPDATE_FIRST keeps the first
+ * order);  GNN_GIN: out = act(((1+eps) X + sum_N X) W + b).  X float[n*in_dim], W float[in_dim*out_dim]
+ * row-major, b NULL or float[out_dim], out float[n*out_dim].  The intermediate lives in the workspace
+ * (size it with max_dim = max(in_dim, out_dim)).  ew is used by GNN_GCN only, eps by GNN_GIN only. */
 int gnn_layer_forward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
                       const float *ew, float eps, const float *X, int32_t in_dim, const float *W,
                       const float *b, int32_t out_dim, int relu, float *out, int32_t ngs, int32_t dw,
