@@ -35,8 +35,9 @@ struct AggParams {
     int stream_out;  // 1: write output rows with streaming stores
     int plain_rows;  // 1: a finished row is stored as it is (no bias, activation or scaling) with streaming stores
     int full_rows;   // 1: one pass, every lane of a team in range: dim == chunks * dw * vector width
-    int extra_blocks;  // one-block-per-tile kernel: blocks appended to the grid for the rows without entries
-    int64_t tile_blocks;  // one-block-per-tile kernel: blocks that serve tiles
+    int extra_blocks;  // blocks of the grid that serve the rows without entries (the first ones; the block-tile
+                       // fused layer appends them)
+    int64_t tile_blocks;  // blocks that serve tiles
     int64_t nnz;
     uint64_t rowptr_key;  // address of the caller's rowptr: the graph the stored partition must belong to
 };

@@ -32,10 +32,6 @@
 #include "gnn_bench.h"
 #include "gnn_launch.h"
 
-#ifndef GNN_EMPTY_FIRST
-#define GNN_EMPTY_FIRST 1
-#endif
-
 namespace gnn {
 
 // Rows the main kernel will not store plainly: rows without entries get their final value, rows
@@ -253,23 +249,14 @@ __global__ __launch_bounds__(1024) void k_aggregate(AggParams p)
     int *s_more = s_last + kMaxWavesPerBlock;                     // [16]: the node continues behind this wave
     int *s_list = s_more + kMaxWavesPerBlock;                     // [nw][64]
 
-#if GNN_EMPTY_FIRST
     if ((int)blockIdx.x < p.extra_blocks) {
-        // the first blocks of the grid: rows without entries (independent of every tile; a multiple of the
-        // number of XCDs, so that block b - extra_blocks still runs on XCD b mod 8)
+        // the first blocks of the grid: rows without entries (independent of every tile; first, so that their
+        // dependent steps do not run as a tail after the last tile; a multiple of the number of XCDs, so that
+        // block b - extra_blocks still runs on XCD b mod 8)
         write_empty_rows<VEC, SELF>(p, (int64_t)blockIdx.x * nw + wave, (int64_t)p.extra_blocks * nw, s_list + wave * 64);
         return;
     }
     const int64_t bid = (int64_t)blockIdx.x - p.extra_blocks;
-#else
-    if ((int64_t)blockIdx.x >= p.tile_blocks) {
-        // blocks appended to the grid: rows without entries (independent of every tile)
-        const int64_t eb = (int64_t)blockIdx.x - p.tile_blocks;
-        write_empty_rows<VEC, SELF>(p, eb * nw + wave, (int64_t)p.extra_blocks * nw, s_list + wave * 64);
-        return;
-    }
-    const int64_t bid = blockIdx.x;
-#endif
     int64_t tile = bid;
     if (p.xcd_remap) {
         // Blocks are dealt to the eight XCDs round-robin by index.  Give every XCD runs of kXcdRun
