@@ -48,3 +48,23 @@ def test_the_json_line_carries_the_required_objects():
                 '"scaling"', '"vs_baseline"', '"dtype"', '"data"', '"config"', '"roofline"', '"cpu_baseline"', '"bound"',
                 '"achieved"', '"peak"', '"frac"', '"traffic"'):
         assert key in src, key
+
+
+def test_every_command_quoted_in_profiles_uses_options_that_bench_defines():
+    src = _bench_source()
+    defined = set(re.findall(r'add_argument\("(--[a-z0-9-]+)"', src))
+    assert "--config" in defined and "--steps" in defined
+    prof = os.path.join(ROOT, "profiles")
+    seen = 0
+    for name in sorted(os.listdir(prof)):
+        assert name.endswith((".md", ".txt")), name  # summaries only, nothing that runs
+        text = open(os.path.join(prof, name)).read()
+        assert "rocprofv3" in text, name  # each summary gives the command that made it
+        for line in text.splitlines():
+            if "bench.py" not in line or "rocprofv3" not in line:
+                continue
+            args = line.split("bench.py", 1)[1]
+            for opt in re.findall(r"(--[a-z0-9-]+)", args):
+                assert opt in defined, (name, opt)
+                seen += 1
+    assert seen > 20
