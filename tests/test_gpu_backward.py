@@ -95,6 +95,50 @@ def test_gin_layer_backward_parity(name, K, M, relu, eps):
     assert_parity(db, rb, sb, f"gin db {name}")
 
 
+@pytest.mark.parametrize("kind", ["gcn", "gin"])
+@pytest.mark.parametrize("n,K,M,relu", [(1, 64, 64, True), (17, 36, 64, True), (1000, 64, 40, False), (4099, 48, 52, True),
+                                        (70001, 64, 64, True), (33000, 60, 36, False)])
+def test_widths_that_take_the_one_pass_update_backward(kind, n, K, M, relu):
+    # widths in (32, 64] that are multiples of 4: dW, db and the input gradient of the Update come from one
+    # kernel that never stores the masked gradient; row counts with ragged 16-row chunks and idle blocks
+    rp, ci = _directed(n, 4.0, n)
+    rng = np.random.default_rng(n + K)
+    X = features(n, K, seed=K + 5)
+    W = glorot(K, M, seed=M + 5)
+    dY = features(n, M, seed=K + M + 5)
+    if kind == "gcn":
+        ew = rng.uniform(0.1, 1.0, ci.size).astype(np.float32)
+        Y = oracle.gcn_layer(rp, ci, ew, X, W, None, relu)
+        refs, scales = oracle.gcn_layer_backward(rp, ci, ew, X, W, relu, Y, dY, want_abs=True)
+        got = _run_backward(gnn.GNN_GCN, rp, ci, ew, 0.0, X, W, relu, Y, dY)
+    else:
+        A = oracle.aggregate_gin(rp, ci, 0.25, X)
+        Y = oracle.gemm_bias_act(A, W, None, relu)
+        refs, scales = oracle.gin_layer_backward(rp, ci, 0.25, A, W, relu, Y, dY, want_abs=True)
+        got = _run_backward(gnn.GNN_GIN, rp, ci, None, 0.25, A, W, relu, Y, dY)
+    for g, r, sc, name in zip(got, refs, scales, ("dX", "dW", "db")):
+        assert_parity(g, r, sc, f"{kind} {name} n {n} {K}->{M}")
+
+
+def test_one_pass_update_backward_is_exact_on_integer_data():
+    # small integers: every product and sum is exact in fp32, so a misplaced row, column or mask bit shows as a
+    # whole number and cannot hide inside the tolerance
+    n, K, M = 5000, 64, 64
+    rp, ci = _directed(n, 3.0, 7)
+    rng = np.random.default_rng(3)
+    A = rng.integers(-3, 4, size=(n, K)).astype(np.float32)
+    W = rng.integers(-2, 3, size=(K, M)).astype(np.float32)
+    dY = rng.integers(-3, 4, size=(n, M)).astype(np.float32)
+    Y = oracle.gemm_bias_act(A, W, None, True)
+    (rX, rW, rb), _ = oracle.gin_layer_backward(rp, ci, 0.0, A, W, True, Y, dY, want_abs=True)
+    dX, dW, db = _run_backward(gnn.GNN_GIN, rp, ci, None, 0.0, A, W, True, Y, dY)
+    assert np.array_equal(dW, rW.astype(np.float32)) and np.array_equal(db, rb.astype(np.float32))
+    assert np.array_equal(dX, rX.astype(np.float32))
+    # without the optional outputs (the first layer of a model wants neither dX nor, here, db)
+    none_x, dW2, none_b = _run_backward(gnn.GNN_GIN, rp, ci, None, 0.0, A, W, True, Y, dY, want_dx=False, want_db=False)
+    assert none_x is None and none_b is None and np.array_equal(dW2, dW)
+
+
 def test_backward_without_optional_outputs_and_on_a_symmetric_graph():
     # a symmetric graph with symmetric weights is its own transpose: the forward CSR can be passed as is
     g = config_graph(4, shrink=32)
