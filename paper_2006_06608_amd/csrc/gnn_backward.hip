@@ -77,7 +77,8 @@ __global__ __launch_bounds__(256) void k_gemm_tn_partial(int n, int K, int M, co
     const int lrow = lane & 15, lk = lane >> 4;
     const int kg = blockIdx.y / mgroups, mg = blockIdx.y % mgroups;
     const int k0 = kg * 16 * KT, m0 = mg * 16 * MT;
-    const int64_t rows = (((int64_t)n + gridDim.x - 1) / gridDim.x + 3) / 4 * 4;
+    constexpr int kSteps = 4;  // 4-row MFMA steps whose loads are issued together
+    const int64_t rows = (((int64_t)n + gridDim.x - 1) / gridDim.x + 4 * kSteps - 1) / (4 * kSteps) * (4 * kSteps);
     const int64_t r0 = (int64_t)blockIdx.x * rows;
     const int64_t r1 = r0 + rows < n ? r0 + rows : n;
 
@@ -87,24 +88,30 @@ __global__ __launch_bounds__(256) void k_gemm_tn_partial(int n, int K, int M, co
 #pragma unroll
         for (int b = 0; b < MT; ++b) acc[a][b] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    for (int64_t r = r0 + 4 * wave; r < r1; r += 4 * kTnWaves) {
-        const int64_t row = r + lk;
-        const bool rv = row < r1;
-        float av[KT], bv[MT];
+    for (int64_t r = r0 + 4 * kSteps * wave; r < r1; r += 4 * kSteps * kTnWaves) {
+        float av[kSteps][KT], bv[kSteps][MT];
 #pragma unroll
-        for (int a = 0; a < KT; ++a) {
-            const int k = k0 + a * 16 + lrow;
-            av[a] = (rv && k < K) ? P[(size_t)row * K + k] : 0.0f;
+        for (int u = 0; u < kSteps; ++u) {
+            const int64_t row = r + 4 * u + lk;
+            const bool rv = row < r1;
+#pragma unroll
+            for (int a = 0; a < KT; ++a) {
+                const int k = k0 + a * 16 + lrow;
+                av[u][a] = (rv && k < K) ? P[(size_t)row * K + k] : 0.0f;
+            }
+#pragma unroll
+            for (int b = 0; b < MT; ++b) {
+                const int m = m0 + b * 16 + lrow;
+                bv[u][b] = (rv && m < M) ? Q[(size_t)row * M + m] : 0.0f;
+            }
         }
 #pragma unroll
-        for (int b = 0; b < MT; ++b) {
-            const int m = m0 + b * 16 + lrow;
-            bv[b] = (rv && m < M) ? Q[(size_t)row * M + m] : 0.0f;
-        }
+        for (int u = 0; u < kSteps; ++u)
 #pragma unroll
-        for (int a = 0; a < KT; ++a)
+            for (int a = 0; a < KT; ++a)
 #pragma unroll
-            for (int b = 0; b < MT; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+                for (int b = 0; b < MT; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][a], bv[u][b], acc[a][b], 0, 0, 0);
     }
 
     // lane holds result rows 4*(lane/16)+i, column lane%16 of each tile
@@ -379,21 +386,26 @@ static int gemm_tn(int32_t n, int32_t K, int32_t M, const float *P, const float 
                    hipStream_t s)
 {
     const dim3 block(64 * kTnWaves);
-    const bool v4 = K % 4 == 0 && M % 4 == 0 && ((uintptr_t)P | (uintptr_t)Q) % 16 == 0;
+    // the 16-byte form spreads 64 columns over a lane group's 16 accumulator tiles: with 32 columns or fewer on
+    // either side half of its MFMAs and more are padding, and the 4-byte form is the faster one (measured)
+    const bool v4 = K > 32 && M > 32 && K % 4 == 0 && M % 4 == 0 && ((uintptr_t)P | (uintptr_t)Q) % 16 == 0;
     if (v4) {
         const int kgroups = (K + 63) / 64, mgroups = (M + 63) / 64;
         hipLaunchKernelGGL(k_gemm_tn_partial_v4, dim3(kTnBlocks, (unsigned)(kgroups * mgroups)), block, 0, s, n, K, M, P, Q,
                            partials, mgroups);
     } else {
-        // tiles per wave: 4 x up to 4 (16 accumulators of 4 registers)
+        // tiles per wave: up to 4 x up to 4 (16 accumulators of 4 registers)
         const int ktiles = (K + 15) / 16, mtiles = (M + 15) / 16;
         const int MT = mtiles >= 4 ? 4 : (mtiles >= 2 ? 2 : 1);
-        const int KT = 4;
+        const int KT = ktiles >= 3 ? 4 : (ktiles == 2 ? 2 : 1);
         const int kgroups = (ktiles + KT - 1) / KT, mgroups = (mtiles + MT - 1) / MT;
         const dim3 grid(kTnBlocks, (unsigned)(kgroups * mgroups));
-        if (MT == 4) hipLaunchKernelGGL((k_gemm_tn_partial<4, 4>), grid, block, 0, s, n, K, M, P, Q, partials, mgroups);
-        else if (MT == 2) hipLaunchKernelGGL((k_gemm_tn_partial<4, 2>), grid, block, 0, s, n, K, M, P, Q, partials, mgroups);
-        else hipLaunchKernelGGL((k_gemm_tn_partial<4, 1>), grid, block, 0, s, n, K, M, P, Q, partials, mgroups);
+#define GNN_TN_CASE(kt, mt) \
+    if (KT == kt && MT == mt) hipLaunchKernelGGL((k_gemm_tn_partial<kt, mt>), grid, block, 0, s, n, K, M, P, Q, partials, mgroups)
+        GNN_TN_CASE(4, 4); GNN_TN_CASE(4, 2); GNN_TN_CASE(4, 1);
+        GNN_TN_CASE(2, 4); GNN_TN_CASE(2, 2); GNN_TN_CASE(2, 1);
+        GNN_TN_CASE(1, 4); GNN_TN_CASE(1, 2); GNN_TN_CASE(1, 1);
+#undef GNN_TN_CASE
     }
     reduce_all(kTnPartials, (int64_t)K * M, partials, C, s);
     GNN_HIP_TRY(hipGetLastError());
