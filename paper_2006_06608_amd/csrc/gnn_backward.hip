@@ -18,6 +18,7 @@ constexpr int kBfWaves = 4;
 constexpr int kBfPartials = kBfBlocks * kBfWaves;
 constexpr int kBfLd = 68;       // floats per LDS row of 64 (16-byte reads of a column block stay conflict-poor)
 constexpr int kRedGroups = 32;  // first level of the sum over partial arrays
+constexpr int kColsumBlocks = 1024;  // row chunks of the bias gradient
 
 // dZ = dY where the forward output was positive, else 0 (derivative of ReLU through its output).
 __global__ __launch_bounds__(256) void k_relu_mask(int64_t total, const float *__restrict__ dY,
@@ -27,16 +28,32 @@ __global__ __launch_bounds__(256) void k_relu_mask(int64_t total, const float *_
         dZ[i] = Y[i] > 0.0f ? dY[i] : 0.0f;
 }
 
-// Column sums of G[n,M], stage 1: block b sums its row chunk into part[b][M].
+// Column sums of G[n,M], stage 1: block b sums its row chunk into part[b][M].  The 256 threads share the
+// columns (up to 256 at a time) and, where there are fewer columns than threads, the rows: thread t takes column
+// t % width and the rows r0 + t / width, + 256 / width, ...; the row lanes' sums meet in LDS in a fixed order.
 __global__ __launch_bounds__(256) void k_colsum_partial(int n, int M, const float *__restrict__ G, float *__restrict__ part)
 {
+    __shared__ float red[256];
     const int64_t rows = ((int64_t)n + gridDim.x - 1) / gridDim.x;
     const int64_t r0 = (int64_t)blockIdx.x * rows;
     const int64_t r1 = r0 + rows < n ? r0 + rows : n;
-    for (int c = threadIdx.x; c < M; c += blockDim.x) {
+    for (int c0 = 0; c0 < M; c0 += 256) {
+        const int width = M - c0 < 256 ? M - c0 : 256;
+        const int lanes = 256 / width;
+        const int c = threadIdx.x % width, rs = threadIdx.x / width;
         float s = 0.0f;
-        for (int64_t r = r0; r < r1; ++r) s += G[(size_t)r * M + c];
-        part[(size_t)blockIdx.x * M + c] = s;
+        if (rs < lanes) {
+#pragma unroll 4
+            for (int64_t r = r0 + rs; r < r1; r += lanes) s += G[(size_t)r * M + c0 + c];
+        }
+        red[threadIdx.x] = s;
+        __syncthreads();
+        if ((int)threadIdx.x < width) {
+            float t = 0.0f;
+            for (int j = 0; j < lanes; ++j) t += red[j * width + threadIdx.x];
+            part[(size_t)blockIdx.x * M + c0 + threadIdx.x] = t;
+        }
+        __syncthreads();
     }
 }
 
@@ -435,7 +452,7 @@ static BwdLayout bwd_layout(int32_t n, int64_t nnz, int32_t in_dim, int32_t out_
     off += align_up(sizeof(float) * (size_t)in_dim * out_dim);
     B.partials = off;
     size_t pb = sizeof(float) * (size_t)(kTnPartials + kRedGroups) * in_dim * out_dim;
-    const size_t bb = sizeof(float) * (size_t)kTnBlocks * out_dim;
+    const size_t bb = sizeof(float) * (size_t)(kColsumBlocks + kRedGroups) * out_dim;
     if (pb < bb) pb = bb;
     if (bwd_fused_shape(in_dim, out_dim))  // partial dW and db of every wave of the one-pass kernel
         pb = sizeof(float) * (size_t)(kBfPartials + kRedGroups) * ((size_t)in_dim * out_dim + out_dim);
@@ -500,9 +517,8 @@ int gnn_layer_backward(int kind, int32_t n, int64_t nnz, const int32_t *rowptr_t
         dZ = dZbuf;
     }
     if (db) {
-        hipLaunchKernelGGL(k_colsum_partial, dim3(kTnBlocks), dim3(256), 0, s, n, out_dim, dZ, partials);
-        hipLaunchKernelGGL(k_reduce_partials, dim3((unsigned)((out_dim + 255) / 256)), dim3(256), 0, s, kTnBlocks,
-                           (int64_t)out_dim, partials, db);
+        hipLaunchKernelGGL(k_colsum_partial, dim3(kColsumBlocks), dim3(256), 0, s, n, out_dim, dZ, partials);
+        reduce_all(kColsumBlocks, (int64_t)out_dim, partials, db, s);
     }
     hipLaunchKernelGGL(k_transpose, dim3((unsigned)((in_dim * out_dim + 255) / 256)), dim3(256), 0, s, in_dim, out_dim, W,
                        Wt);
