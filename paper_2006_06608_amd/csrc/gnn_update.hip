@@ -194,6 +194,155 @@ __global__ __launch_bounds__(256) void k_update_gemm(GemmParams p)
     }
 }
 
+// More than 64 columns and many rows: a block owns 128 rows x 128 columns and a wave 64 x 64 of them (4 x 4
+// tiles of 16 x 16), so that one 16-byte LDS read of A serves four column tiles and one of W four row tiles
+// (the kernel above reads 4 bytes of W per MFMA and A once per 64 columns).  A and W travel in chunks of 32
+// along K (registers, then LDS).  The four column tiles of a lane are interleaved -- tile t holds the columns
+// c0 + 4*(lane%16) + t -- so that the lane's W operands are one float4 of a row of W, and its results four
+// consecutive columns: 16-byte stores.  Any K in one launch.
+template <bool AV4, bool WV4>
+__global__ __launch_bounds__(256, 2) void k_update_gemm_tile(GemmParams p)
+{
+    constexpr int KC = 32, BR = 128, BC = 128, LDA = KC + 4, LDB = BC + 4, NT = 256;
+    constexpr int FA = BR * KC / 4 / NT, FB = KC * BC / 4 / NT;  // float4 per thread and chunk: 4 and 4
+    __shared__ __attribute__((aligned(16))) float s_A[BR * LDA];
+    __shared__ __attribute__((aligned(16))) float s_B[KC * LDB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int lrow = lane & 15, lk = lane >> 4;
+    const int col0 = blockIdx.y * BC;
+    const int kpad = (p.K + KC - 1) / KC * KC;
+    const int64_t ntiles = ((int64_t)p.n + BR - 1) / BR;
+
+    float4 pa[FA], pb[FB];
+    auto fetch = [&](int64_t row0, int kc) {
+#pragma unroll
+        for (int i = 0; i < FA; ++i) {
+            const int e = tid + NT * i, r = e / (KC / 4), c = (e % (KC / 4)) * 4;
+            const int64_t row = row0 + r;
+            const int k = kc + c;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < p.n) {
+                const float *src = p.A + (size_t)row * p.K + k;
+                if (AV4) {
+                    if (k < p.K) v = *reinterpret_cast<const float4 *>(src);
+                } else {
+                    if (k < p.K) v.x = src[0];
+                    if (k + 1 < p.K) v.y = src[1];
+                    if (k + 2 < p.K) v.z = src[2];
+                    if (k + 3 < p.K) v.w = src[3];
+                }
+            }
+            pa[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < FB; ++i) {
+            const int e = tid + NT * i, kr = e / (BC / 4), c = (e % (BC / 4)) * 4;
+            const int k = kc + kr, col = col0 + c;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < p.K) {
+                const float *src = p.W + (size_t)k * p.M + col;
+                if (WV4) {
+                    if (col < p.M) v = *reinterpret_cast<const float4 *>(src);
+                } else {
+                    if (col < p.M) v.x = src[0];
+                    if (col + 1 < p.M) v.y = src[1];
+                    if (col + 2 < p.M) v.z = src[2];
+                    if (col + 3 < p.M) v.w = src[3];
+                }
+            }
+            pb[i] = v;
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < FA; ++i) {
+            const int e = tid + NT * i;
+            *reinterpret_cast<float4 *>(&s_A[(e / (KC / 4)) * LDA + (e % (KC / 4)) * 4]) = pa[i];
+        }
+#pragma unroll
+        for (int i = 0; i < FB; ++i) {
+            const int e = tid + NT * i;
+            *reinterpret_cast<float4 *>(&s_B[(e / (BC / 4)) * LDB + (e % (BC / 4)) * 4]) = pb[i];
+        }
+    };
+
+    const int col = col0 + wc * 64 + 4 * lrow;  // first of the lane's four result columns
+    float bias[4] = {0.f, 0.f, 0.f, 0.f};
+    if (p.b) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (col + t < p.M) bias[t] = p.b[col + t];
+    }
+
+    if ((int64_t)blockIdx.x < ntiles) fetch((int64_t)blockIdx.x * BR, 0);
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t row0 = tile * BR;
+        f32x4 acc[4][4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[a][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+        for (int kc = 0; kc < kpad; kc += KC) {
+            __syncthreads();  // the previous chunk is consumed
+            commit();
+            __syncthreads();
+            // the next chunk -- of this tile or the first of the block's next tile -- travels during the MFMAs
+            if (kc + KC < kpad) fetch(row0, kc + KC);
+            else if (tile + gridDim.x < ntiles) fetch((tile + gridDim.x) * BR, 0);
+#pragma unroll
+            for (int ks = 0; ks < KC; ks += 16) {
+                // the lane's reduction indices are k = ks + 4*lk + s, s = 0..3, on both operands
+                float av[4][4];
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const float4 v = *reinterpret_cast<const float4 *>(&s_A[(wr * 64 + a * 16 + lrow) * LDA + ks + 4 * lk]);
+                    av[a][0] = v.x;
+                    av[a][1] = v.y;
+                    av[a][2] = v.z;
+                    av[a][3] = v.w;
+                }
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) {
+                    const float4 w = *reinterpret_cast<const float4 *>(&s_B[(ks + 4 * lk + s4) * LDB + wc * 64 + 4 * lrow]);
+                    const float bv[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                    for (int a = 0; a < 4; ++a)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            acc[a][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a][s4], bv[t], acc[a][t], 0, 0, 0);
+                }
+            }
+        }
+
+        // lane holds rows 4*lk + i of row tile a and, over the four column tiles, the columns col .. col + 3
+        if (col < p.M) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t row = row0 + wr * 64 + a * 16 + 4 * lk + i;
+                    if (row >= p.n) continue;
+                    float v[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        v[t] = acc[a][t][i] + bias[t];
+                        if (p.relu) v[t] = fmaxf(v[t], 0.0f);
+                    }
+                    float *o = p.out + (size_t)row * p.M + col;
+                    if (WV4 && (((uintptr_t)p.out) & 15) == 0) {  // M % 4 == 0: the four columns exist and are aligned
+                        *reinterpret_cast<float4 *>(o) = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (col + t < p.M) o[t] = v[t];
+                    }
+                }
+        }
+    }
+}
+
 // Few rows (at most one 64-row tile per block) and K >= 128: nothing is gained by keeping W in LDS
 // for the life of the block, so the W rows of each K chunk travel with the A chunk (registers, then
 // LDS), any K is one launch, and the chunk is wide (128, or 64 for 64 columns) so that a block has
@@ -613,6 +762,25 @@ int update_gemm_impl(int32_t n, int32_t K, int32_t M, const float *A, const floa
         if (MT == 1) launch_gemm_few<1, 128>(vec4, wv4, grid, s, p);
         else if (MT == 2) launch_gemm_few<2, 128>(vec4, wv4, grid, s, p);
         else launch_gemm_few<4, 64>(vec4, wv4, grid, s, p);
+        GNN_HIP_TRY(hipGetLastError());
+        return GNN_OK;
+    }
+    if (M > 64 && n >= kGemmFewRows) {  // wide and tall: 128 x 128 tiles, two resident blocks per CU walk over the rows
+        GemmParams p;
+        p.A = A; p.W = W; p.b = b; p.out = out;
+        p.n = n; p.K = K; p.M = M;
+        p.k_begin = 0; p.k_end = K; p.accumulate = 0; p.finish = 1;
+        p.relu = relu;
+        const bool wv4 = (M % 4 == 0) && ((uintptr_t)W % 16 == 0);
+        int dev = 0, cus = 0;
+        GNN_HIP_TRY(hipGetDevice(&dev));
+        GNN_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        const int64_t rt = ((int64_t)n + 127) / 128, cap_t = (int64_t)2 * (cus > 0 ? cus : 256);
+        const dim3 grid((unsigned)(rt < cap_t ? rt : cap_t), (unsigned)((M + 127) / 128));
+        if (vec4 && wv4) hipLaunchKernelGGL((k_update_gemm_tile<true, true>), grid, dim3(256), 0, s, p);
+        else if (vec4) hipLaunchKernelGGL((k_update_gemm_tile<true, false>), grid, dim3(256), 0, s, p);
+        else if (wv4) hipLaunchKernelGGL((k_update_gemm_tile<false, true>), grid, dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((k_update_gemm_tile<false, false>), grid, dim3(256), 0, s, p);
         GNN_HIP_TRY(hipGetLastError());
         return GNN_OK;
     }

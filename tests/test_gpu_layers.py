@@ -15,7 +15,9 @@ if torch.cuda.is_available():
 
 @pytest.mark.parametrize("n,K,M", [(1, 1, 1), (63, 5, 3), (64, 16, 3), (1000, 500, 16), (777, 96, 16), (4097, 64, 64),
                                    (300, 16, 22), (129, 33, 70), (200, 700, 40), (50, 1323, 7), (3001, 300, 33),
-                                   (65535, 256, 8), (70000, 260, 16), (5000, 512, 32), (33000, 256, 20)])
+                                   (65535, 256, 8), (70000, 260, 16), (5000, 512, 32), (33000, 256, 20),
+                                   (70001, 64, 128), (66000, 128, 128), (66000, 130, 200), (70000, 33, 65), (4000, 256, 256),
+                                   (65536, 100, 70), (65537, 8, 300)])
 @pytest.mark.parametrize("relu,bias", [(False, False), (True, True)])
 def test_update_gemm_parity(n, K, M, relu, bias):
     rng = np.random.default_rng(n + K + M)
